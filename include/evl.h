@@ -269,6 +269,12 @@ evl_status evl_pages_copy(evl_cache *cache, void *dst_k, void *dst_v, const int3
                           int32_t dst_pool_pages, const void *src_k, const void *src_v,
                           const int32_t *src_pages, int32_t src_pool_pages, int32_t n);
 
+/* =========================================================================================
+ * DIAGNOSTICS.  Everything from here to the end of the header serves measurement and tests
+ * (bench.py, the planner tests): none of it is part of the method, none of it is needed to use
+ * the library, and none of it changes a result beyond rounding order.
+ * ========================================================================================= */
+
 /*
  * How the last evl_chunk_attention[_batched] call on `cache` was (or the next identical one
  * would be) partitioned: number of attention work-groups, largest split count of any

@@ -20,6 +20,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <mutex>
 #include <type_traits>
 
 namespace evl {
@@ -1810,17 +1811,33 @@ hipError_t launch_rope_append(const AppendParams &p, int head_dim, hipStream_t s
     return hipGetLastError();
 }
 
+// Kernels whose dynamic LDS exceeds 64 KB need the limit raised first: once per kernel and
+// device, whichever host thread gets there first (the outcome of that one try is kept).
+constexpr int kMaxDevices = 64;
+struct LargeLdsOnce {
+    std::once_flag once[kMaxDevices];
+    hipError_t result[kMaxDevices];
+};
+static hipError_t allow_large_lds(const void *fn, LargeLdsOnce &st) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::call_once(st.once[dev], [&] {
+        st.result[dev] = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    return st.result[dev];
+}
+
 // ev_start / ev_stop (both or neither): events the runtime stamps with the begin and the end of
 // this very dispatch (not of the stream around it).
 template <int D, int QB, bool MULTI>
 static hipError_t launch_attn(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     const size_t lds = attention_lds_bytes(D, p.tab_tokens, MULTI);
-    static bool attr_set = false;
-    if (lds > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_kernel<D, QB, MULTI>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LargeLdsOnce large_lds;
+    if (lds > 64 * 1024) {
+        hipError_t e = allow_large_lds((const void *)attn_kernel<D, QB, MULTI>, large_lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const dim3 grid(p.items_per_xcd * 8), block(kRowsPerWorkgroup / (32 * QB) * 64);
     if (ev_start)
@@ -1885,14 +1902,13 @@ hipError_t launch_decode_attention(const AttnParams &p, int head_dim, int n_work
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
     if (fused) {
-        static bool step_attr_set[2] = {false, false};
+        static LargeLdsOnce step_large_lds[2];
         const int si = head_dim == 128 ? 0 : 1;
         const void *sfn =
             head_dim == 128 ? (const void *)decode_step_kernel<128> : (const void *)decode_step_kernel<64>;
-        if (lds > 64 * 1024 && !step_attr_set[si]) {
-            hipError_t e = hipFuncSetAttribute(sfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (lds > 64 * 1024) {
+            hipError_t e = allow_large_lds(sfn, step_large_lds[si]);
             if (e != hipSuccess) return e;
-            step_attr_set[si] = true;
         }
         const dim3 sgrid(n_workgroups + fused->n_items), sblock(kDecodeWaves * 64);
         if (ev_start) {
@@ -1909,13 +1925,12 @@ hipError_t launch_decode_attention(const AttnParams &p, int head_dim, int n_work
         }
         return hipGetLastError();
     }
-    static bool attr_set[2] = {false, false};
+    static LargeLdsOnce large_lds[2];
     const int idx = head_dim == 128 ? 0 : 1;
     const void *fn = head_dim == 128 ? (const void *)decode_kernel<128> : (const void *)decode_kernel<64>;
-    if (lds > 64 * 1024 && !attr_set[idx]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (lds > 64 * 1024) {
+        hipError_t e = allow_large_lds(fn, large_lds[idx]);
         if (e != hipSuccess) return e;
-        attr_set[idx] = true;
     }
     const dim3 grid(n_workgroups), block(kDecodeWaves * 64);
     if (ev_start) {
