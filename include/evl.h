@@ -138,6 +138,23 @@ evl_status evl_chunk_attention(const void *q_new, evl_cache *cache, int32_t cach
                                int32_t n_new, void *out);
 
 /*
+ * evl_chunk_attention for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc -- and so cannot hand the cache
+ * a workspace: the partial results of the key-range pieces and the ticket counters live in a
+ * static device array of the library (16 MiB + 4 KiB per GPU, held until the process ends)
+ * instead of cache->workspace, which this call neither reads nor writes.  Same arguments, same
+ * checks and the same result as evl_chunk_attention on a cache whose workspace has that size
+ * (the key range is cut into as many pieces as fit); sequence 0.  Chunks of more than 8192
+ * (token, query head) rows (n_new * n_q_heads) are refused with EVL_ERR_WORKSPACE.  The call
+ * allocates and frees nothing, on the device or through any library.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ * race; calls on one stream are safe.  Whatever must start at zero is cleared by the call
+ * itself, with a fill kernel on the stream.
+ */
+evl_status evl_chunk_attention_static(const void *q_new, evl_cache *cache, int32_t cache_len,
+                                      int32_t n_new, void *out);
+
+/*
  * Ragged batch: the same two operations for n_seqs independent sequences in one launch
  * sequence.  Inputs and outputs are concatenated along the token axis in the order of the
  * arrays (sequence seq_ids[0]'s n_new[0] tokens first, and so on).  seq_ids, pos_offsets,

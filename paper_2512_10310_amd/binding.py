@@ -25,7 +25,7 @@ EXPORTS = ["evl_cache_create", "evl_cache_destroy", "evl_cache_reset", "evl_cach
            "evl_chunk_attention_sampled", "evl_workspace_bytes_sampled", "evl_sample_uniform",
            "evl_sample_window", "evl_chunk_attention_sampled_batched", "evl_isolated_pack_attention",
            "evl_pages_copy", "evl_step", "evl_step_batched", "evl_step_sampled",
-           "evl_cache_launches"]
+           "evl_cache_launches", "evl_chunk_attention_static"]
 
 
 def status_name(code: int) -> str:
@@ -89,6 +89,7 @@ def declare(L):
     L.evl_last_error.restype = C.c_char_p
     L.evl_rope_append.argtypes = [vp, vp, vp, i64, i32]
     L.evl_chunk_attention.argtypes = [vp, vp, i32, i32, vp]
+    L.evl_chunk_attention_static.argtypes = [vp, vp, i32, i32, vp]
     L.evl_rope_append_batched.argtypes = [vp, vp, vp, pi32, pi64, pi32, i32]
     L.evl_chunk_attention_batched.argtypes = [vp, vp, pi32, pi32, pi32, i32, vp]
     L.evl_last_plan.argtypes = [vp, pi32, pi32, C.POINTER(C.c_size_t)]
@@ -216,6 +217,9 @@ class Cache:
 
     def chunk_attention(self, q_new, cache_len: int, n_new: int, out) -> None:
         _check(load().evl_chunk_attention(_ptr(q_new), self._h, int(cache_len), int(n_new), _ptr(out)))
+
+    def chunk_attention_static(self, q_new, cache_len: int, n_new: int, out) -> None:
+        _check(load().evl_chunk_attention_static(_ptr(q_new), self._h, int(cache_len), int(n_new), _ptr(out)))
 
     def step(self, q_new, k_new, v_new, pos_offset: int, n_new: int, out) -> None:
         _check(load().evl_step(self._h, _ptr(q_new), _ptr(k_new), _ptr(v_new), int(pos_offset), int(n_new),

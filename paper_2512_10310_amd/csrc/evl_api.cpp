@@ -759,6 +759,37 @@ evl_status evl_chunk_attention(const void *q_new, evl_cache *cache, int32_t cach
     return evl_chunk_attention_batched(q_new, cache, &seq, &cache_len, &n_new, 1, out);
 }
 
+// The same call for callers that cannot allocate device memory: partial results and ticket
+// counters live in the library's own static device array instead of the cache's workspace.
+evl_status evl_chunk_attention_static(const void *q_new, evl_cache *c, int32_t cache_len, int32_t n_new,
+                                      void *out) {
+    if (!c) return fail(EVL_ERR_NULL, "cache is NULL");
+    if (n_new > 0 && (int64_t)n_new * c->d.n_q_heads > evl::kStaticScratchMaxRows)
+        return fail(EVL_ERR_WORKSPACE,
+                    "evl_chunk_attention_static serves chunks of at most %d (token, query head) rows; "
+                    "%d tokens x %d heads = %lld", evl::kStaticScratchMaxRows, n_new, c->d.n_q_heads,
+                    (long long)n_new * c->d.n_q_heads);
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    hipError_t e = evl::static_scratch(&ptr, &bytes);
+    if (e != hipSuccess)
+        return fail(EVL_ERR_LAUNCH, "the static scratch array is not available: %s", hipGetErrorString(e));
+    // The array is shared by every call on this GPU and keeps what the last one left: the ticket
+    // counters are cleared (by a fill kernel on the stream) whenever this call is going to use them.
+    void *const ws = c->d.workspace;
+    const size_t ws_bytes = c->d.workspace_bytes;
+    const bool zeroed = c->counters_zeroed;
+    c->d.workspace = ptr;
+    c->d.workspace_bytes = bytes;
+    c->counters_zeroed = false;
+    const int32_t seq = 0;
+    const evl_status st = evl_chunk_attention_batched(q_new, c, &seq, &cache_len, &n_new, 1, out);
+    c->d.workspace = ws;
+    c->d.workspace_bytes = ws_bytes;
+    c->counters_zeroed = zeroed;
+    return st;
+}
+
 // ------------------------------------------------------------------------------------------
 // A whole step: append, then attend from the appended chunk
 // ------------------------------------------------------------------------------------------

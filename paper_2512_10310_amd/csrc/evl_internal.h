@@ -161,4 +161,13 @@ hipError_t launch_pages_copy(const PageCopyParams &p, hipStream_t stream);
 constexpr int kCounters = 1024;         // ticket counters kept in the last 4 KB of the workspace
 constexpr size_t kCounterBytes = 4096;
 
+// ---- the library's own scratch array (for callers that cannot allocate) ------------------------
+// A file-scope device array that stands in for the caller's workspace: room for the partial rows
+// of one chunk plus the ticket counters.  Every GPU the library runs on holds one copy until the
+// process ends.
+constexpr size_t kStaticScratchBytes = ((size_t)16 << 20) + kCounterBytes;
+constexpr int kStaticScratchMaxRows = 8192;  // (token, query head) rows of a chunk served from it
+// Device address and size of the current device's copy of the array (looked up once per device).
+hipError_t static_scratch(void **ptr, size_t *bytes);
+
 }  // namespace evl

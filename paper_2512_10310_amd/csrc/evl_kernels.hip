@@ -1890,6 +1890,33 @@ __global__ void zero_counters_kernel(int *counters, int n) {
     if (i < n) counters[i] = 0;
 }
 
+// The library's own scratch array: the workspace of the entry point that allocates nothing.
+// In host code the array's name is only a handle of the symbol; its device address differs from
+// GPU to GPU and comes from hipGetSymbolAddress, asked once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void **ptr, size_t *bytes) {
+    static std::mutex mu;
+    static void *dev_ptr[kMaxDevices] = {};
+    *ptr = nullptr;
+    *bytes = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_ptr[dev]) {
+        void *a = nullptr;
+        e = hipGetSymbolAddress(&a, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!a) return hipErrorInvalidSymbol;
+        dev_ptr[dev] = a;
+    }
+    *ptr = dev_ptr[dev];
+    *bytes = kStaticScratchBytes;
+    return hipSuccess;
+}
+
 hipError_t launch_zero_counters(int *counters, int n, hipStream_t stream) {
     hipLaunchKernelGGL(zero_counters_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, counters, n);
     return hipGetLastError();

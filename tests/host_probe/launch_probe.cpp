@@ -342,6 +342,15 @@ hipError_t launch_zero_counters(int *counters, int n, hipStream_t) {
     return hipSuccess;
 }
 
+// (a host array of the real size stands in for the device array: the checks above only compare
+// addresses and sizes)
+hipError_t static_scratch(void **ptr, size_t *bytes) {
+    static std::vector<unsigned char> fake(kStaticScratchBytes + 256);
+    *ptr = (void *)(((uintptr_t)fake.data() + 255) & ~(uintptr_t)255);
+    *bytes = kStaticScratchBytes;
+    return hipSuccess;
+}
+
 hipError_t launch_pages_copy(const PageCopyParams &p, hipStream_t) {
     ++g_count[5];
     REQUIRE(p.n >= 1 && p.n <= kMaxPagesPerCopy && p.page_bytes > 0 && p.page_bytes % 16 == 0, "pages_copy: %d pages of %d bytes",
