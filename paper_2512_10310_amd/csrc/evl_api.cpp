@@ -433,6 +433,76 @@ static evl_status launch_attention(evl_cache *c, const evl::AttnParams &p) {
     return EVL_OK;
 }
 
+// One key range the rows attend to, with the position at which the queries are rotated for it.
+struct Entry { int32_t begin, stop, causal; int64_t q_pos; int tiles; };
+
+// ------------------------------------------------------------------------------------------
+// Rows that see fewer than kFewKeys keys (the first tokens of a sequence, or of a sparsely
+// sampled history) are served by a kernel of their own, in fp32; every call peels them off its
+// chunks before it plans the matrix kernels, and hands those the rest of each chunk as a chunk
+// that starts that many tokens later (the same result: how a chunk is cut never matters).
+// ------------------------------------------------------------------------------------------
+// Number of leading tokens of a chunk whose rows see fewer than kFewKeys keys, if `before` keys
+// are visible to all of the chunk's tokens: token i sees before + i + 1.
+static int32_t few_tokens(int64_t before, int32_t n_new) {
+    return (int32_t)std::max<int64_t>(0, std::min<int64_t>(n_new, evl::kFewKeys - 1 - before));
+}
+
+struct FewGroup {
+    int32_t bt_row, cache_len, n_few, tok_off;  // the group's first n_few tokens are served here
+    std::vector<Entry> ent;                     // its key ranges, the causal one last
+};
+
+// Writes group g's entries into the launch's entry table from index `at` on.
+static void fill_few_group(const evl_cache *c, evl::AttnParams *p, int at, const FewGroup &g) {
+    for (size_t i = 0; i < g.ent.size(); ++i) {
+        evl::AttnSeq &q = p->seq[at + (int)i];
+        std::memset(&q, 0, sizeof(q));
+        q.bt_row = g.bt_row;
+        q.cache_len = g.cache_len;
+        q.n_new = g.n_few;
+        q.tok_off = g.tok_off;
+        q.k_begin = g.ent[i].begin;
+        // (the causal range ends with the last token served here)
+        q.k_stop = g.ent[i].causal ? std::min(g.ent[i].stop, g.cache_len + g.n_few) : g.ent[i].stop;
+        q.causal = g.ent[i].causal;
+        q.q_pos = (int32_t)g.ent[i].q_pos;
+        q.n_ent = i == 0 ? (int32_t)g.ent.size() : 0;
+    }
+}
+
+// The groups from *next on ride along with an attention launch, as many as its entry table still
+// has room for (behind the launch's own p->n_seqs entries, which must be final); *next advances.
+static void attach_few(const evl_cache *c, evl::AttnParams *p, const std::vector<FewGroup> &groups, size_t *next) {
+    int at = p->n_seqs;
+    p->few_first = at;
+    while (*next < groups.size() && at + (int)groups[*next].ent.size() <= evl::kMaxEntries) {
+        const FewGroup &g = groups[*next];
+        fill_few_group(c, p, at, g);
+        at += (int)g.ent.size();
+        p->few_rows += g.n_few * c->d.n_q_heads;
+        ++*next;
+    }
+    p->few_entries = at - p->few_first;
+}
+
+// The groups from `next` on in launches of their own.
+static evl_status few_keys_attention(evl_cache *c, const void *q_new, void *out, const std::vector<FewGroup> &groups,
+                                     size_t next = 0) {
+    while (next < groups.size()) {
+        evl::AttnParams p;
+        evl::CombineParams cp;
+        // (partial results and counters are not used: every row is finished by its own wave)
+        init_params(c, q_new, out, nullptr, nullptr, &p, &cp);
+        attach_few(c, &p, groups, &next);
+        hipError_t e = evl::launch_few_keys(p, c->d.head_dim, (hipStream_t)c->d.stream);
+        if (e == hipSuccess) ++c->n_launches;
+        if (e != hipSuccess)
+            return fail(EVL_ERR_LAUNCH, "few-keys attention launch failed: %s", hipGetErrorString(e));
+    }
+    return EVL_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // Chunks of a few tokens (at most 32 packed rows per KV head): the decode kernel, one wave per
 // piece of the key range.  `ents`: the key ranges the rows attend to (one per sequence in the
@@ -564,6 +634,10 @@ static evl_status decode_attention(evl_cache *c, const void *q_new, void *out,
     return EVL_OK;
 }
 
+static evl_status attention_batched_core(const void *q_new, evl_cache *c, const int32_t *seq_ids,
+                                         const int32_t *cache_lens, const int32_t *n_new, const int32_t *tok_offs_in,
+                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few);
+
 evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const int32_t *seq_ids,
                                        const int32_t *cache_lens, const int32_t *n_new,
                                        int32_t n_seqs, void *out) {
@@ -589,6 +663,38 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
                         cache_lens[i], n_new[i], (long long)c->len[s]);
     }
 
+    // rows that see fewer than kFewKeys keys go to their own kernel; the matrix kernels get what
+    // is left of each chunk
+    std::vector<int32_t> ids, lens, ns, offs;
+    std::vector<FewGroup> few;
+    int64_t off = 0;
+    for (int i = 0; i < n_seqs; ++i) {
+        const int32_t a = few_tokens(cache_lens[i], n_new[i]);
+        if (a > 0)
+            few.push_back(FewGroup{seq_ids[i], cache_lens[i], a, (int32_t)off,
+                                   {Entry{0, cache_lens[i] + a, 1, c->pos0[seq_ids[i]] + cache_lens[i], 0}}});
+        if (a < n_new[i]) {
+            ids.push_back(seq_ids[i]);
+            lens.push_back(cache_lens[i] + a);
+            ns.push_back(n_new[i] - a);
+            offs.push_back((int32_t)(off + a));
+        }
+        off += n_new[i];
+    }
+    if (ids.empty()) {
+        c->last_plan = Plan();
+        return few_keys_attention(c, q_new, out, few);
+    }
+    return attention_batched_core(q_new, c, ids.data(), lens.data(), ns.data(), offs.data(), (int32_t)ids.size(), out,
+                                  few);
+}
+
+// The plain call on chunks whose rows all see at least kFewKeys keys (arguments checked by the
+// caller); tok_offs[i]: first token of chunk i in q_new / out.  few: the rows that were peeled
+// off, which travel with the first attention launch(es) or, behind the decode kernel, alone.
+static evl_status attention_batched_core(const void *q_new, evl_cache *c, const int32_t *seq_ids,
+                                         const int32_t *cache_lens, const int32_t *n_new, const int32_t *tok_offs_in,
+                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few) {
     const int D = c->d.head_dim, Hq = c->d.n_q_heads, Hkv = c->d.n_kv_heads, G = c->group;
     const int MT = evl::attention_rows_per_workgroup();
     const int KN = evl::kKeyTile;
@@ -597,17 +703,16 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
     {
         std::vector<DecodeEntry> ents(n_seqs);
         std::vector<int> first(n_seqs + 1);
-        int64_t off = 0;
         for (int i = 0; i < n_seqs; ++i) {
-            ents[i] = DecodeEntry{seq_ids[i], cache_lens[i], n_new[i], (int32_t)off, 0, cache_lens[i] + n_new[i], 1,
+            ents[i] = DecodeEntry{seq_ids[i], cache_lens[i], n_new[i], tok_offs_in[i], 0, cache_lens[i] + n_new[i], 1,
                                   c->pos0[seq_ids[i]] + cache_lens[i]};
             first[i] = i;
-            off += n_new[i];
         }
         first[n_seqs] = n_seqs;
         bool done = false;
         evl_status st = decode_attention(c, q_new, out, ents, first, &done);
-        if (st != EVL_OK || done) return st;
+        if (st != EVL_OK) return st;
+        if (done) return few_keys_attention(c, q_new, out, few);
     }
 
     // ---- partition: one split length (in key tiles) for the whole launch, so that every
@@ -676,11 +781,9 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
     std::vector<int> order(n_seqs);
     std::vector<int64_t> tok_offs(n_seqs);
     {
-        int64_t off = 0;
         for (int i = 0; i < n_seqs; ++i) {
             order[i] = i;
-            tok_offs[i] = off;
-            off += n_new[i];
+            tok_offs[i] = tok_offs_in[i];
         }
         std::stable_sort(order.begin(), order.end(),
                          [&](int a, int b) { return tiles[a] > tiles[b]; });
@@ -692,13 +795,14 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
 
     Plan plan;
     plan.workspace_used = ws_rows * row_bytes;
-    size_t part_off = 0;
+    size_t part_off = 0, few_next = 0;
     for (int base = 0; base < n_seqs; base += evl::kMaxSeqs) {
         const int cnt = std::min(evl::kMaxSeqs, n_seqs - base);
         evl::AttnParams p;
         evl::CombineParams cp;
         init_params(c, q_new, out, part_o, part_ml, &p, &cp);
         p.n_seqs = cnt;
+        attach_few(c, &p, few, &few_next);
         int items = 0, crow = 0, cseqs = 0;
         int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         for (int i = 0; i < cnt; ++i) {
@@ -750,7 +854,7 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
         }
     }
     c->last_plan = plan;
-    return EVL_OK;
+    return few_keys_attention(c, q_new, out, few, few_next);
 }
 
 evl_status evl_chunk_attention(const void *q_new, evl_cache *cache, int32_t cache_len,
@@ -802,8 +906,11 @@ evl_status evl_step_batched(evl_cache *c, const void *q_new, const void *k_new, 
     if (st != EVL_OK) return st;
     std::vector<int32_t> cache_lens(n_seqs);
     for (int i = 0; i < n_seqs; ++i) cache_lens[i] = (int32_t)c->len[seq_ids[i]];
-    // chunks of a few tokens everywhere: one launch appends and attends
-    if (n_seqs <= evl::kMaxSeqs) {
+    // chunks of a few tokens everywhere: one launch appends and attends (unless some sequence is
+    // still so short that its rows go to the few-keys kernel)
+    bool short_history = false;
+    for (int i = 0; i < n_seqs; ++i) short_history = short_history || few_tokens(cache_lens[i], n_new[i]) > 0;
+    if (n_seqs <= evl::kMaxSeqs && !short_history) {
         std::vector<DecodeEntry> ents(n_seqs);
         std::vector<int> first(n_seqs + 1);
         int64_t off = 0;
@@ -840,9 +947,6 @@ evl_status evl_step(evl_cache *cache, const void *q_new, const void *k_new, cons
 // ------------------------------------------------------------------------------------------
 // Chunk attention over a sampled history
 // ------------------------------------------------------------------------------------------
-// One key range the rows attend to, with the position at which the queries are rotated for it.
-struct Entry { int32_t begin, stop, causal; int64_t q_pos; int tiles; };
-
 // Key tiles of the attention kernel that cover an entry's key range: the tiles start at the page
 // that holds the range's first key (the kernel derives the same from the range).
 static int entry_tiles(int32_t begin, int32_t stop) {
@@ -922,6 +1026,27 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
     if (st != EVL_OK) return st;
     const int E = (int)ent.size();
 
+    // rows that see fewer than kFewKeys keys (a sparse history and the chunk's first tokens) go to
+    // their own kernel; what follows sees the rest of the chunk, which starts tok0 tokens later
+    int32_t tok0 = 0;
+    std::vector<FewGroup> few;
+    size_t few_next = 0;
+    {
+        int64_t retained = 0;
+        for (int r = 0; r < n_runs; ++r) retained += runs[r].len;
+        tok0 = few_tokens(retained, n_new);
+        if (tok0 > 0) {
+            few.push_back(FewGroup{seq, cache_len, tok0, 0, ent});
+            if (tok0 == n_new) {
+                c->last_plan = Plan();
+                return few_keys_attention(c, q_new, out, few);
+            }
+            for (Entry &e : ent) e.q_pos += tok0;
+            cache_len += tok0;
+            n_new -= tok0;
+        }
+    }
+
     const int D = c->d.head_dim, Hq = c->d.n_q_heads, Hkv = c->d.n_kv_heads, G = c->group;
     const int MT = evl::attention_rows_per_workgroup();
     const int m_tiles = (n_new * G + MT - 1) / MT;
@@ -930,11 +1055,12 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
     {
         std::vector<DecodeEntry> dents(E);
         for (int i = 0; i < E; ++i)
-            dents[i] = DecodeEntry{seq, cache_len, n_new, 0, ent[i].begin, ent[i].stop, ent[i].causal, ent[i].q_pos};
+            dents[i] = DecodeEntry{seq, cache_len, n_new, tok0, ent[i].begin, ent[i].stop, ent[i].causal, ent[i].q_pos};
         const std::vector<int> first = {0, E};
         bool done = false;
         st = decode_attention(c, q_new, out, dents, first, &done);
-        if (st != EVL_OK || done) return st;
+        if (st != EVL_OK) return st;
+        if (done) return few_keys_attention(c, q_new, out, few);
     }
 
     // ---- partition.  The entries' key tiles are laid end to end and cut into pieces of one
@@ -990,13 +1116,14 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
         init_params(c, q_new, out, part_o, part_ml, &p, &cp);
         p.n_seqs = cnt;
         p.multi_entry = cnt > 1;
+        attach_few(c, &p, few, &few_next);
         for (int i = 0; i < cnt; ++i) {
             const Entry &e = ent[base + i];
             evl::AttnSeq &q = p.seq[i];
             q.bt_row = seq;
             q.cache_len = cache_len;
             q.n_new = n_new;
-            q.tok_off = 0;
+            q.tok_off = tok0;
             q.k_begin = e.begin;
             q.k_stop = e.stop;
             q.causal = e.causal;
@@ -1022,7 +1149,7 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
         cp.n_seqs = 1;
         cp.n_rows = n_new * Hq;
         cp.seq[0].n_new = n_new;
-        cp.seq[0].tok_off = 0;
+        cp.seq[0].tok_off = tok0;
         cp.seq[0].n_splits = total_splits;
         cp.seq[0].row_begin = 0;
         cp.seq[0].part_off = 0;
@@ -1033,7 +1160,7 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
     }
     plan.max_splits = total_splits;
     c->last_plan = plan;
-    return EVL_OK;
+    return few_keys_attention(c, q_new, out, few, few_next);
 }
 
 // The sampled call as a whole step: append, then attend over the retained runs and the chunk.
@@ -1048,7 +1175,9 @@ evl_status evl_step_sampled(evl_cache *c, const void *q_new, const void *k_new, 
     st = build_entries(c, seq, runs, n_runs, cache_len, n_new, &ent, false, pos_offset);
     if (st != EVL_OK) return st;
     const int E = (int)ent.size();
-    if (E <= evl::kMaxSeqs) {
+    int64_t retained = 0;
+    for (int r = 0; r < n_runs; ++r) retained += runs[r].len;
+    if (E <= evl::kMaxSeqs && few_tokens(retained, n_new) == 0) {
         std::vector<DecodeEntry> dents(E);
         for (int i = 0; i < E; ++i)
             dents[i] = DecodeEntry{seq, cache_len, n_new, 0, ent[i].begin, ent[i].stop, ent[i].causal, ent[i].q_pos,
@@ -1084,47 +1213,71 @@ evl_status evl_step_sampled(evl_cache *c, const void *q_new, const void *k_new, 
 // Several (sequence, runs, chunk) groups in one call.  A group's entries stay together in one
 // launch (at most kMaxEntries entries and kMaxSeqs groups per launch); all groups share one
 // piece length.
-evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, int32_t n_groups,
-                                               const int32_t *seq_ids, const int32_t *cache_lens,
-                                               const int32_t *n_new, const int32_t *tok_offs,
+evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, int32_t n_groups_in,
+                                               const int32_t *seq_ids_in, const int32_t *cache_lens_in,
+                                               const int32_t *n_new_in, const int32_t *tok_offs,
                                                const int32_t *run_offsets, const evl_run *runs, void *out) {
     if (!c) return fail(EVL_ERR_NULL, "cache is NULL");
     if (!q_new || !out) return fail(EVL_ERR_NULL, "q_new / out is NULL");
-    if (!seq_ids || !cache_lens || !n_new || !run_offsets) return fail(EVL_ERR_NULL, "a host array is NULL");
+    if (!seq_ids_in || !cache_lens_in || !n_new_in || !run_offsets) return fail(EVL_ERR_NULL, "a host array is NULL");
     if (!aligned16(q_new) || !aligned16(out))
         return fail(EVL_ERR_ALIGN, "q_new / out must be 16-byte aligned");
-    if (n_groups <= 0) return fail(EVL_ERR_ARG, "n_groups = %d must be positive", n_groups);
+    if (n_groups_in <= 0) return fail(EVL_ERR_ARG, "n_groups = %d must be positive", n_groups_in);
 
     const int D = c->d.head_dim, Hq = c->d.n_q_heads, Hkv = c->d.n_kv_heads, G = c->group;
     const int MT = evl::attention_rows_per_workgroup();
     struct Group { int first, count, m_tiles, n_splits, tps; int64_t tiles; int32_t tok_off; };
     std::vector<Entry> ent;       // all groups' entries, group after group
-    std::vector<Group> grp(n_groups);
+    std::vector<Group> grp;
+    std::vector<FewGroup> few;    // the leading tokens of groups whose rows see fewer than kFewKeys keys
+    std::vector<int32_t> g_seq, g_len, g_new;  // the groups the matrix kernels serve (what is left of each chunk)
     int64_t tok = 0;
-    for (int g = 0; g < n_groups; ++g) {
+    for (int g = 0; g < n_groups_in; ++g) {
         if (run_offsets[g + 1] < run_offsets[g])
             return fail(EVL_ERR_ARG, "run_offsets must not decrease (group %d)", g);
         std::vector<Entry> e;
-        evl_status st = build_entries(c, seq_ids[g], runs ? runs + run_offsets[g] : nullptr,
-                                      run_offsets[g + 1] - run_offsets[g], cache_lens[g], n_new[g], &e);
+        const evl_run *g_runs = runs ? runs + run_offsets[g] : nullptr;
+        const int32_t g_n_runs = run_offsets[g + 1] - run_offsets[g];
+        evl_status st = build_entries(c, seq_ids_in[g], g_runs, g_n_runs, cache_lens_in[g], n_new_in[g], &e);
         if (st != EVL_OK) return st;
         if ((int)e.size() > evl::kMaxSeqs)
             return fail(EVL_ERR_UNSUPPORTED, "group %d has %d runs with different shifts; a batched call takes "
                                              "at most %d per group", g, (int)e.size(), evl::kMaxSeqs);
         if (tok_offs && (tok_offs[g] < 0 || ((int64_t)tok_offs[g] * Hq * D * 2) % 16))
             return fail(EVL_ERR_ARG, "tok_offs[%d] = %d", g, tok_offs[g]);
-        grp[g].first = (int)ent.size();
-        grp[g].count = (int)e.size();
-        grp[g].m_tiles = (n_new[g] * G + MT - 1) / MT;
-        grp[g].tok_off = tok_offs ? tok_offs[g] : (int32_t)tok;
-        grp[g].tiles = 0;
+        const int32_t g_tok = tok_offs ? tok_offs[g] : (int32_t)tok;
+        tok += n_new_in[g];
+        int64_t retained = 0;
+        for (int r = 0; r < g_n_runs; ++r) retained += g_runs[r].len;
+        const int32_t a = few_tokens(retained, n_new_in[g]);
+        if (a > 0) few.push_back(FewGroup{seq_ids_in[g], cache_lens_in[g], a, g_tok, e});
+        if (a == n_new_in[g]) continue;
+        Group gr;
+        gr.first = (int)ent.size();
+        gr.count = (int)e.size();
+        gr.m_tiles = ((n_new_in[g] - a) * G + MT - 1) / MT;
+        gr.tok_off = g_tok + a;
+        gr.tiles = 0;
+        gr.n_splits = 1;
+        gr.tps = 0;
         for (Entry &x : e) {
+            x.q_pos += a;
             x.tiles = entry_tiles(x.begin, x.stop);
-            grp[g].tiles += x.tiles;
+            gr.tiles += x.tiles;
         }
         ent.insert(ent.end(), e.begin(), e.end());
-        tok += n_new[g];
+        grp.push_back(gr);
+        g_seq.push_back(seq_ids_in[g]);
+        g_len.push_back(cache_lens_in[g] + a);
+        g_new.push_back(n_new_in[g] - a);
     }
+    if (grp.empty()) {
+        c->last_plan = Plan();
+        return few_keys_attention(c, q_new, out, few);
+    }
+    size_t few_next = 0;
+    const int n_groups = (int)grp.size();
+    const int32_t *seq_ids = g_seq.data(), *cache_lens = g_len.data(), *n_new = g_new.data();
 
     // chunks of a few tokens everywhere: the decode kernel
     if ((int)ent.size() <= evl::kMaxSeqs) {
@@ -1139,7 +1292,8 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
         first[n_groups] = (int)ent.size();
         bool done = false;
         evl_status st = decode_attention(c, q_new, out, dents, first, &done);
-        if (st != EVL_OK || done) return st;
+        if (st != EVL_OK) return st;
+        if (done) return few_keys_attention(c, q_new, out, few);
     }
 
     // ---- partition: one piece length for all groups, as in the plain batched call ----
@@ -1196,6 +1350,7 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
         init_params(c, q_new, out, part_o, part_ml, &p, &cp);
         p.n_seqs = n_ent;
         p.multi_entry = 1;
+        attach_few(c, &p, few, &few_next);
         int items = 0, crow = 0, cseqs = 0, at = 0;
         int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         for (int g = g0; g < g1; ++g) {
@@ -1250,7 +1405,7 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
         g0 = g1;
     }
     c->last_plan = plan;
-    return EVL_OK;
+    return few_keys_attention(c, q_new, out, few, few_next);
 }
 
 // Packed sequence under the action-isolating mask: the instruction and every step of the pack

@@ -78,6 +78,10 @@ struct AttnParams {
     int32_t tab_tokens;  // tokens the LDS cos/sin table of a work-group has room for
     float q_scale;   // log2(e) / sqrt(d), folded into the rotated queries
     int32_t multi_entry;  // 1 if some group of this launch has more than one entry
+    // Groups of rows that see fewer than kFewKeys keys: entries seq[few_first .. few_first +
+    // few_entries), few_rows (token, query head) rows in all.  In an attention launch they ride
+    // along as extra work-groups behind the 8 * items_per_xcd of the matrix part.
+    int32_t few_first, few_entries, few_rows;
     double rev_freq[kMaxHalfDim];  // theta_j / (2 pi): turns per position
     AttnSeq seq[kMaxEntries];
 };
@@ -146,6 +150,16 @@ hipError_t launch_decode_attention(const AttnParams &p, int head_dim, int n_work
                                    hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr,
                                    const AppendParams *fused = nullptr);
 hipError_t launch_combine(const CombineParams &p, int head_dim, hipStream_t stream);
+// Rows that see fewer than kFewKeys keys (the first tokens of a sequence) do not go through the
+// bf16 matrix pipes: with so few keys nothing averages out the rounding of the rotated queries
+// and of the probabilities to bf16, so those rows get plain fp32 arithmetic, one wave per row
+// (the rotated keys in the cache stay what they are).  Entries as in an attention launch (groups
+// of key ranges with their query positions; n_new = the group's tokens served here, all of which
+// see fewer than kFewKeys keys), named by few_first / few_entries / few_rows.  This launcher
+// starts the kernel on its own; launch_chunk_attention takes such groups along with its matrix
+// work, as extra work-groups of the same launch.
+constexpr int kFewKeys = 64;
+hipError_t launch_few_keys(const AttnParams &p, int head_dim, hipStream_t stream);
 hipError_t launch_zero_counters(int *counters, int n, hipStream_t stream);
 
 // ---- page copies between pools ---------------------------------------------------------------

@@ -362,6 +362,148 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(const AppendParam
 }
 
 // =========================================================================================
+// Rows that see fewer than 64 keys.  One wave per (token, query head) row, everything in fp32:
+// lane f rotates the query's channel pair of frequency f (per entry, at that entry's query
+// position) into a wave-private LDS row; lane j owns the j-th visible key, counted through the
+// group's entries, and forms its score as a plain dot product with the stored (rotated) key;
+// maximum and sum go over the lanes; then lane c accumulates channels c (and c + 64) of the
+// output over the keys.  No barrier: waves are independent.
+// =========================================================================================
+// (the body serves two kernels: row = index of the wave's row among the launch's few-keys rows;
+// qs: D floats of LDS of the wave's own)
+template <int D>
+__device__ __forceinline__ void few_keys_body(const AttnParams &p, int row, float *qs) {
+    const int lane = threadIdx.x & 63;
+    const int G = p.group, Hq = p.n_q_heads, Hkv = p.n_kv_heads;
+    if (row >= p.few_rows) return;
+    int s = p.few_first;  // first entry of the row's group
+    for (;;) {
+        if (s >= p.few_first + p.few_entries || p.seq[s].n_ent <= 0) return;  // (few_rows is the groups' row count: never taken)
+        const int rows_here = p.seq[s].n_new * Hq;
+        if (row < rows_here) break;
+        row -= rows_here;
+        s += p.seq[s].n_ent;
+    }
+    const AttnSeq sq = p.seq[s];
+    const int i = row / Hq, hq = row - i * Hq, kvh = hq / G;
+    const int f = lane & (D / 2 - 1);  // (D = 64: the upper half of the wave repeats the lower)
+    const bf16 *qrow = (const bf16 *)p.q + ((size_t)(sq.tok_off + i) * Hq + hq) * D;
+    const float qa = (float)qrow[f], qb = (float)qrow[f + D / 2];
+    const double rev_freq = p.rev_freq[f];
+    const int32_t *bt = p.block_table + (size_t)sq.bt_row * p.max_pages_per_seq;
+
+    int n_keys = 0, my_t = 0, my_pid = 0;
+    bool mine = false, is_first = false;  // is_first: the first key of its range
+    float score = -INFINITY;  // log2 domain
+    for (int e = s; e < s + sq.n_ent; ++e) {
+        const int kb = p.seq[e].k_begin;
+        const int ks = p.seq[e].causal ? min(p.seq[e].k_stop, sq.cache_len + i + 1) : p.seq[e].k_stop;
+        const int len = ks - kb;
+        if (len <= 0) continue;
+        const float2 cs = rope_cos_sin(p.seq[e].q_pos + i, rev_freq);
+        // (a wave's LDS accesses are served in order: the reads below see these writes, and the
+        // next entry's writes come after this entry's reads)
+        qs[f] = qa * cs.x - qb * cs.y;
+        qs[f + D / 2] = qb * cs.x + qa * cs.y;
+        asm volatile("" ::: "memory");
+        const int jj = lane - n_keys;
+        if (jj >= 0 && jj < len) {
+            mine = true;
+            is_first = jj == 0;
+            my_t = kb + jj;
+            my_pid = clamp_page(bt[my_t / kPage], p.n_pages);
+            const bf16 *krow =
+                (const bf16 *)p.k_pool + (((size_t)my_pid * Hkv + kvh) * kPage + my_t % kPage) * D;
+            float acc = 0.f;
+#pragma unroll
+            for (int c = 0; c < D / 8; ++c) {
+                const bf16x8 kk = *(const bf16x8 *)(krow + 8 * c);
+#pragma unroll
+                for (int x = 0; x < 8; ++x) acc = fmaf(qs[8 * c + x], (float)kk[x], acc);
+            }
+            score = acc * p.q_scale;
+        }
+        asm volatile("" ::: "memory");
+        n_keys += len;
+    }
+    n_keys = min(n_keys, 64);  // (the host sends only rows with fewer than 64 keys)
+
+    float m = score;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    const float pj = mine ? __builtin_amdgcn_exp2f(score - m) : 0.f;
+    float l = pj;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+
+    // Values: [page][head][channel][16 tokens], so the (up to 16) keys that share a page are 32
+    // contiguous bytes per channel.  The visible keys fall into page segments (a segment starts
+    // where a key range starts or a page does); lane c takes channel c (and c + 64) and walks
+    // through the segments four at a time, all loads of a round first.  Which lane holds a
+    // segment's first key comes from a ballot; its page, first token and the weights are read
+    // from that lane and its successors (wave-uniform reads, no memory access).
+    const bool head_of_segment = mine && (my_t % kPage == 0 || is_first);
+    unsigned long long heads = __ballot(head_of_segment);
+    constexpr int CB = D == 128 ? 2 : 1;  // 64-channel blocks per lane
+    float o[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) o[cb] = 0.f;
+    const bf16 *v_pool = (const bf16 *)p.v_pool;
+    const int pj_bits = __float_as_int(pj);
+    while (heads) {
+        int h0[4], cnt[4], slot0[4];
+        bf16x8 w0[4][CB], w1[4][CB];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool any = heads != 0;
+            h0[u] = any ? __ffsll(heads) - 1 : 0;
+            heads &= heads - 1;
+            const int next = heads ? __ffsll(heads) - 1 : n_keys;
+            cnt[u] = any ? next - h0[u] : 0;
+            const int pid = __builtin_amdgcn_readlane(my_pid, h0[u]);
+            slot0[u] = __builtin_amdgcn_readlane(my_t, h0[u]) % kPage;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const bf16 *src = v_pool + (((size_t)pid * Hkv + kvh) * D + lane + 64 * cb) * kPage;
+                w0[u][cb] = *(const bf16x8 *)src;
+                w1[u][cb] = *(const bf16x8 *)(src + 8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int sl = 0; sl < kPage; ++sl) {
+                const int k = sl - slot0[u];  // which key of the segment sits in this slot
+                const bool on = k >= 0 && k < cnt[u];
+                const float w = __int_as_float(__builtin_amdgcn_readlane(pj_bits, on ? h0[u] + k : 0));
+                // (slots outside the segment are other tokens' or unused: selected away, not multiplied by zero)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    o[cb] += on ? w * (float)(sl < 8 ? w0[u][cb][sl] : w1[u][cb][sl - 8]) : 0.f;
+            }
+    }
+    const float o0 = o[0], o1 = o[CB - 1];
+    const float inv = 1.0f / l;
+    const size_t o_idx = ((size_t)(sq.tok_off + i) * Hq + hq) * D;
+    if (p.out_f32) {
+        ((float *)p.out)[o_idx + lane] = o0 * inv;
+        if (D == 128) ((float *)p.out)[o_idx + lane + 64] = o1 * inv;
+    } else {
+        ((bf16 *)p.out)[o_idx + lane] = (bf16)(o0 * inv);
+        if (D == 128) ((bf16 *)p.out)[o_idx + lane + 64] = (bf16)(o1 * inv);
+    }
+}
+
+constexpr int kFewRowsPerGroup = 4;  // waves (rows) per work-group of the kernel on its own
+
+template <int D>
+__global__ __launch_bounds__(kFewRowsPerGroup * 64) void few_keys_kernel(const AttnParams p) {
+    __shared__ float q_rot[kFewRowsPerGroup][D];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    few_keys_body<D>(p, blockIdx.x * kFewRowsPerGroup + wave, q_rot[wave]);
+}
+
+// =========================================================================================
 // Chunk attention.
 //
 // Work item = (sequence, KV head, key-range split, row tile).  Rows are the packed pairs
@@ -442,6 +584,13 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     static_assert(T::ITS % PARTS == 0, "page fetch must split evenly over its waves");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+    // Work-groups behind the matrix part serve the rows that see fewer than 64 keys, one per wave.
+    if ((int)blockIdx.x >= p.items_per_xcd * 8) {
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        few_keys_body<D>(p, ((int)blockIdx.x - p.items_per_xcd * 8) * NW + w, (float *)smem + w * D);
+        return;
+    }
 
     // XCD-aware work-group -> work-item map.  The hardware deals work-groups round-robin to
     // the 8 XCDs, each with its own L2: work-group b runs on XCD b % 8 and is that XCD's
@@ -1800,6 +1949,18 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const CombineParams p
 // =========================================================================================
 // Launchers
 // =========================================================================================
+hipError_t launch_few_keys(const AttnParams &p, int head_dim, hipStream_t stream) {
+    if (p.few_rows <= 0) return hipSuccess;
+    const dim3 grid((p.few_rows + kFewRowsPerGroup - 1) / kFewRowsPerGroup), block(kFewRowsPerGroup * 64);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(few_keys_kernel<128>, grid, block, 0, stream, p);
+    else if (head_dim == 64)
+        hipLaunchKernelGGL(few_keys_kernel<64>, grid, block, 0, stream, p);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_rope_append(const AppendParams &p, int head_dim, hipStream_t stream) {
     if (p.n_items <= 0) return hipSuccess;
     if (head_dim == 128)
@@ -1839,7 +2000,8 @@ static hipError_t launch_attn(const AttnParams &p, hipStream_t stream, hipEvent_
         hipError_t e = allow_large_lds((const void *)attn_kernel<D, QB, MULTI>, large_lds);
         if (e != hipSuccess) return e;
     }
-    const dim3 grid(p.items_per_xcd * 8), block(kRowsPerWorkgroup / (32 * QB) * 64);
+    constexpr int NW = kRowsPerWorkgroup / (32 * QB);
+    const dim3 grid(p.items_per_xcd * 8 + (p.few_rows + NW - 1) / NW), block(NW * 64);
     if (ev_start)
         hipExtLaunchKernelGGL((attn_kernel<D, QB, MULTI>), grid, block, (uint32_t)lds, stream, ev_start, ev_stop, 0, p);
     else
@@ -1849,7 +2011,7 @@ static hipError_t launch_attn(const AttnParams &p, hipStream_t stream, hipEvent_
 
 hipError_t launch_chunk_attention(const AttnParams &p, int head_dim, hipStream_t stream, hipEvent_t ev_start,
                                   hipEvent_t ev_stop) {
-    if (p.n_items <= 0) return hipSuccess;
+    if (p.n_items <= 0 && p.few_rows <= 0) return hipSuccess;
     if (head_dim == 128)
         return p.multi_entry ? launch_attn<128, 1, true>(p, stream, ev_start, ev_stop)
                              : launch_attn<128, 1, false>(p, stream, ev_start, ev_stop);

@@ -21,7 +21,7 @@ from paper_2512_10310_amd import binding  # noqa: E402
 
 Q, K, V, OUT = 0x10000000, 0x20000000, 0x30000000, 0x40000000
 KPOOL, VPOOL, TABLE, WS = 0x100000000, 0x200000000, 0x300000000, 0x400000000
-KINDS = ["append", "attention", "decode", "combine", "zero_counters", "pages_copy"]
+KINDS = ["append", "attention", "decode", "combine", "zero_counters", "pages_copy", "few_keys"]
 
 
 def main(path, seed0, n_seeds):
@@ -30,12 +30,12 @@ def main(path, seed0, n_seeds):
     probe.evl_probe_count.restype = C.c_int64
     probe.evl_probe_pending.restype = C.c_int64
     binding._lib = probe              # this process only ever sees the probe
-    totals = np.zeros(6, dtype=np.int64)
+    totals = np.zeros(len(KINDS), dtype=np.int64)
     for seed in range(seed0, seed0 + n_seeds):
         totals += episode(probe, seed)
     print("launches checked:", ", ".join("%s %d" % kv for kv in zip(KINDS, totals)), flush=True)
     # every kind of launch the episodes can reach was reached
-    assert all(totals[:5] > 0), totals
+    assert all(totals[:5] > 0) and totals[6] > 0, totals
     return 0
 
 
@@ -211,7 +211,7 @@ def episode(probe, seed):
             assert c.len(s) == lens[s], "%s\n  sequence %d: library length %d, model %d" % (what, s, c.len(s), lens[s])
             if lens[s] > 0:
                 assert c.pos0(s) == pos0[s], "%s\n  sequence %d: pos0 %d, model %s" % (what, s, c.pos0(s), pos0[s])
-    counts = np.array([probe.evl_probe_count(k) for k in range(6)], dtype=np.int64)
+    counts = np.array([probe.evl_probe_count(k) for k in range(len(KINDS))], dtype=np.int64)
     assert c.launches() == counts.sum(), "%s\n  library counted %d launches, probe saw %s" % (what, c.launches(), counts)
     print(what, "->", counts.sum(), "launches", flush=True)
     c.close()

@@ -21,7 +21,7 @@
 namespace {
 
 char g_msg[512] = "";
-int64_t g_count[6] = {0, 0, 0, 0, 0, 0};
+int64_t g_count[7] = {0, 0, 0, 0, 0, 0, 0};
 int g_max_seqs = 1;
 
 // rows (of one launch sequence of attention kernels) whose partial results wait for a combine
@@ -94,7 +94,7 @@ void evl_probe_reset(int32_t max_seqs) {
     g_max_seqs = max_seqs;
 }
 const char *evl_probe_message(void) { return g_msg; }
-int64_t evl_probe_count(int32_t kind) { return kind >= 0 && kind < 6 ? g_count[kind] : -1; }
+int64_t evl_probe_count(int32_t kind) { return kind >= 0 && kind < 7 ? g_count[kind] : -1; }
 int64_t evl_probe_pending(void) { return (int64_t)g_pending.size(); }
 }
 
@@ -130,10 +130,16 @@ hipError_t launch_rope_append(const AppendParams &p, int head_dim, hipStream_t) 
     return hipSuccess;
 }
 
+hipError_t check_few(const AttnParams &p, const char *who);
+
 hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEvent_t, hipEvent_t) {
     const char *who = "attention";
     ++g_count[1];
     if (hipError_t e = check_common(p, D, who)) return e;
+    // rows with few keys that ride along: entries behind the launch's own
+    REQUIRE(p.few_entries == 0 || p.few_first == p.n_seqs, "%s: few-keys entries start at %d, own entries end at %d",
+            who, p.few_first, p.n_seqs);
+    if (hipError_t e = check_few(p, who)) return e;
     const int G = p.group, Hq = p.n_q_heads, Hkv = p.n_kv_heads, KN = kKeyTile;
     REQUIRE(p.n_seqs >= 1 && p.n_seqs <= kMaxEntries, "%s: n_seqs %d", who, p.n_seqs);
     const size_t ws_rows = partial_rows(p.part_o, p.part_ml, D, p.out_f32 != 0);
@@ -213,6 +219,54 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
     REQUIRE(p.tab_tokens >= 0, "%s: tab_tokens %d", who, p.tab_tokens);
     REQUIRE(attention_lds_bytes(D, p.tab_tokens, p.multi_entry != 0) <= 160 * 1024, "%s: LDS", who);
     return hipSuccess;
+}
+
+// The few-keys part of a launch gives every row one wave and every visible key one lane: all rows
+// of a group must see fewer than 64 keys, counted through the group's entries, and the entries
+// must be the ones an attention launch would take.
+hipError_t check_few(const AttnParams &p, const char *who) {
+    REQUIRE(p.few_rows >= 0 && p.few_entries >= 0, "%s: few-keys part %d rows, %d entries", who, p.few_rows,
+            p.few_entries);
+    if (p.few_entries == 0) {
+        REQUIRE(p.few_rows == 0, "%s: %d few-keys rows without entries", who, p.few_rows);
+        return hipSuccess;
+    }
+    REQUIRE(p.few_first >= 0 && p.few_first + p.few_entries <= kMaxEntries, "%s: few-keys entries %d + %d", who,
+            p.few_first, p.few_entries);
+    int rows = 0;
+    for (int e = p.few_first; e < p.few_first + p.few_entries;) {
+        const AttnSeq &sq = p.seq[e];
+        REQUIRE(sq.n_ent >= 1 && e + sq.n_ent <= p.few_first + p.few_entries, "%s: few-keys entry %d: group of %d entries",
+                who, e, sq.n_ent);
+        REQUIRE(sq.bt_row >= 0 && sq.bt_row < g_max_seqs, "%s: few-keys entry %d: block-table row %d", who, e, sq.bt_row);
+        REQUIRE(sq.n_new >= 1 && sq.cache_len >= 0 && sq.tok_off >= 0, "%s: few-keys entry %d: chunk", who, e);
+        int64_t before = 0;  // keys every row of the group sees
+        int n_causal = 0;
+        for (int x = e; x < e + sq.n_ent; ++x) {
+            const AttnSeq &en = p.seq[x];
+            if (x > e) REQUIRE(en.n_ent == 0, "%s: few-keys entry %d inside a group heads a group", who, x);
+            if (hipError_t err = check_range(p, sq, en, x, who)) return err;
+            n_causal += en.causal != 0;
+            REQUIRE(!en.causal || x == e + sq.n_ent - 1, "%s: causal few-keys entry %d is not the group's last", who, x);
+            before += (en.causal ? sq.cache_len : en.k_stop) - en.k_begin;
+        }
+        REQUIRE(n_causal == 1, "%s: few-keys entry %d: %d causal entries", who, e, n_causal);
+        REQUIRE(before + sq.n_new < kFewKeys, "%s: few-keys entry %d: the last of %d rows sees %lld keys", who, e,
+                sq.n_new, (long long)(before + sq.n_new));
+        rows += sq.n_new * p.n_q_heads;
+        e += sq.n_ent;
+    }
+    REQUIRE(p.few_rows == rows, "%s: few_rows %d, groups hold %d rows", who, p.few_rows, rows);
+    return hipSuccess;
+}
+
+hipError_t launch_few_keys(const AttnParams &p, int D, hipStream_t) {
+    const char *who = "few keys";
+    ++g_count[6];
+    if (hipError_t e = check_common(p, D, who)) return e;
+    REQUIRE(p.few_rows >= 1 && p.few_first == 0 && p.n_seqs == 0, "%s: %d rows, entries from %d, %d other entries", who,
+            p.few_rows, p.few_first, p.n_seqs);
+    return check_few(p, who);
 }
 
 hipError_t launch_combine(const CombineParams &p, int D, hipStream_t) {

@@ -81,12 +81,10 @@ def test_batch_of_long_and_short_chunks(workspace_bytes):
     print("plan:", layer.cache.last_plan())
     for idx, s in enumerate(order):
         want = osts[s].step(ch[s][0], ch[s][1], ch[s][2], 7 * s + pre[s])
-        keys = pre[s] + 1 + np.arange(new[s])
-        many = keys >= 64
-        if many.any():
-            check_close(got[idx][many], want[many], MAX_ABS, MEAN_ABS, "seq %d" % s)
-        if (~many).any():     # rows with few keys: the operands' rounding noise is not averaged out
-            check_close(got[idx][~many], want[~many], 3e-2, 4e-3, "seq %d, rows with few keys" % s)
+        check_close(got[idx], want, MAX_ABS, MEAN_ABS, "seq %d" % s)
+        few = pre[s] + 1 + np.arange(new[s]) < 64   # (served in fp32; the same bar, on their own as well)
+        if few.any():
+            check_close(got[idx][few], want[few], MAX_ABS, MEAN_ABS, "seq %d, rows with few keys" % s)
 
 
 def test_more_sequences_than_one_launch_describes():
@@ -183,22 +181,20 @@ def test_fixed_window_repeats_are_bit_identical():
         assert np.array_equal(got, first)
 
 
-def test_ragged_batch_full_size_sampled_rows():
-    """The ragged-batch workload at full size: 16 episodes, cached lengths uniform in
-    [2048, 65536], a 204-token chunk each, one launch through a randomly ordered page pool.
-    The oracle checks 3 sampled chunk tokens (all 28 heads) per episode, one episode at a time."""
-    from harness import GpuLayer, check_close
+@pytest.fixture(scope="module")
+def ragged_full_size():
+    """The ragged-batch workload at full size, run once: 16 episodes, cached lengths uniform in
+    [2048, 65536], a 204-token chunk each, ONE launch through a randomly ordered page pool.  Returns
+    what the oracle needs to redo any episode."""
+    from harness import GpuLayer
     shape = LAYER7B
     lens = ragged_cache_lengths(16, 2048, 65536).tolist()
     n = shape.step_tokens
     layer = GpuLayer(shape, [c + n for c in lens], random_pages=True, out_f32=False, cfg=3,
                      workspace_bytes=768 << 20, with_tags=False, poison=False)
     ids = list(range(16))
-    chunk = {}
-    rng = np.random.default_rng(33)
-    worst = 0.0
-    # fill each episode's cache in pieces of at most 8192 tokens, keeping the oracle for one episode only
-    pieces = {}
+    chunk, pieces = {}, {}
+    # fill each episode's cache in pieces of at most 8192 tokens
     for s in ids:
         done, step = 0, 0
         pieces[s] = []
@@ -214,21 +210,47 @@ def test_ragged_batch_full_size_sampled_rows():
     got = layer.attend_batched([chunk[s][0] for s in ids], ids, lens)
     items, splits, ws = layer.cache.last_plan()
     print("ragged plan: %d work-groups, up to %d splits, %.1f MB workspace" % (items, splits, ws / 2 ** 20))
-    for s in ids:
+    assert splits > 1 and items > 2000      # the plan this test is here for: thousands of work-groups, key ranges in pieces
+    del layer
+    torch.cuda.empty_cache()
+    return lens, pieces, chunk, got
+
+
+@pytest.mark.parametrize("part", range(4))
+def test_ragged_batch_full_size(ragged_full_size, part):
+    """Four whole episodes against the oracle, all 204 tokens x 28 heads -- the shortest, the
+    longest and the two around the median -- and of every other episode 64 seeded tokens that
+    always include the first, the last and the tokens around which the packed rows cross a 256-row
+    tile of the kernel.  (Four tests of four episodes each: the oracle takes a while.)"""
+    from harness import check_close
+    shape = LAYER7B
+    lens, pieces, chunk, got = ragged_full_size
+    n = shape.step_tokens
+    by_len = sorted(range(16), key=lambda s: lens[s])
+    whole = {by_len[0], by_len[7], by_len[8], by_len[15]}
+    worst = 0.0
+    for s in range(4 * part, 4 * part + 4):
         ost = oracle.Stream(28, 4, 128, 1e6)
         for m, step in pieces[s]:
             _, k, v = qkv_chunk(shape, m, 3, s, step)
             ost.append(k, v, len(ost))
         ost.append(chunk[s][1], chunk[s][2], lens[s])
-        rows = sorted(set([0, n - 1] + rng.integers(1, n - 1, 1).tolist()))
+        if s in whole:
+            rows = list(range(n))
+        else:
+            rng = np.random.default_rng([33, s])
+            fixed = [0, 36, 73, 109, 146, 182, n - 1]
+            rest = [t for t in rng.permutation(n).tolist() if t not in fixed]
+            rows = sorted(fixed + rest[:64 - len(fixed)])
         want = ost.attend(chunk[s][0], lens[s], rows=rows)
         mx, mn = check_close(got[s][rows], want, MAX_ABS, MEAN_ABS, "episode %d (C=%d)" % (s, lens[s]))
+        print("episode %d: %d cached tokens, %d rows checked, max|diff| %.2e mean %.2e" % (s, lens[s], len(rows), mx, mn),
+              flush=True)
         worst = max(worst, mx)
         del ost
-    print("ragged full size: worst max|diff| over sampled rows %.2e" % worst)
     # Sharper than the workload's bar: with thousands of keys in every row the rounding of keys,
-    # queries and probabilities to bf16 leaves a few 1e-4 at most (3e-4 observed); one lost
-    # 64-key tile of the shortest episode would move its rows by about 3e-3.
+    # queries and probabilities to bf16 leaves a few 1e-4 at most (3e-4 observed on three rows per
+    # episode); one lost 64-key tile of the shortest episode would move its rows by about 3e-3.
     assert worst <= 1.5e-3, worst
 
 

@@ -245,8 +245,9 @@ def test_one_call_step_equals_the_two_calls(C, n):
         got_two = two.step(q, k, v, 5 + at)
         before = one.cache.launches()
         got_one = one.fused_step(q, k, v, 5 + at)
-        # one launch (two the first time a cache object's piece counters are cleared)
-        assert one.cache.launches() - before <= (2 if rnd == 0 else 1)
+        # one launch (two the first time a cache object's piece counters are cleared); while the
+        # sequence is shorter than 64 tokens the rows go to the few-keys kernel: append + that kernel
+        assert one.cache.launches() - before <= (2 if rnd == 0 or at + n < 64 else 1)
         assert one.cache.len() == two.cache.len() == at + n and one.cache.pos0() == 5
         assert np.array_equal(got_one, got_two), "C=%d n=%d round %d" % (C, n, rnd)
         check_close(got_one, want, MAX_ABS, MEAN_ABS, "C=%d n=%d round %d" % (C, n, rnd))
@@ -313,7 +314,9 @@ def test_one_call_step_on_a_ragged_batch(shape):
         before = one.cache.launches()
         got_one = one.fused_step_batched(qs, ks, vs, ids, pos)
         took = one.cache.launches() - before
-        assert took <= 2 if rnd == 0 else took >= 2, took      # short chunks: one launch (+ counter fill)
+        # short chunks: one launch (+ counter fill) -- but two of these sequences are still shorter than
+        # 64 tokens, whose rows go to the few-keys kernel: append, that kernel, the rest (+ counter fill)
+        assert took <= 4 if rnd == 0 else took >= 2, took
         two.append_batched(ks, vs, ids, pos)
         got_two = two.attend_batched(qs, ids, cur)
         for s in ids:

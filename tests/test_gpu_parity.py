@@ -435,7 +435,8 @@ def test_one_call_step_with_a_long_chunk(heads, C, n, ws):
         before = one.cache.launches()
         got_one = one.fused_step(q, k, v, 3 + at)
         took = one.cache.launches() - before
-        assert took <= (2 if n * (Hq // Hkv) <= 32 else 3), took     # append, attention, merge of the pieces
+        # append, attention, merge of the pieces (and the few-keys kernel while the sequence is short)
+        assert took <= (2 if n * (Hq // Hkv) <= 32 else 3) + (1 if at < 63 else 0), took
         assert one.cache.len() == two.cache.len() == at + n and one.cache.pos0() == 3
         assert np.array_equal(got_one, got_two), "round %d" % rnd
         check_close(got_one, want, MAX_ABS, MEAN_ABS, "heads %s C=%d n=%d round %d" % (heads, C, n, rnd))

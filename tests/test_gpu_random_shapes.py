@@ -14,24 +14,26 @@ from synth import StreamShape, qkv_chunk
 pytestmark = pytest.mark.gpu
 
 MAX_ABS, MEAN_ABS = 1e-2, 1e-3
-# Rows that see few keys do not average anything out: the cache holds rotated keys rounded to
-# bf16 and the MFMA takes rotated queries rounded to bf16, which puts an error of about 2^-8.5
-# (standard deviation, in nats) on every score, whatever the kernel does.  Over N comparable
-# keys that leaves about 3e-3 |v| / sqrt(N) on an output: around 1e-3 on average at N = 16 (and
-# 1e-2 in the tail of a few hundred thousand outputs when two or three keys are in play), a
-# third of that at N = 64.  Rows with fewer than 64 visible keys therefore get wider bars; all
-# other rows the bar of the workload.
-FEW_KEYS, MAX_ABS_FEW, MEAN_ABS_FEW = 64, 3e-2, 4e-3
+# Rows that see few keys do not average anything out, and their outputs are O(|v|).  What the
+# path's bf16 roundings leave there was measured on the CPU by rounding the oracle's own tensors
+# (3000 causal blocks of 96 tokens, d = 128, 1.5 million outputs per class of visible keys):
+#   rotated keys, rotated queries and probabilities rounded (the matrix kernel's three): up to
+#   1.5e-2 with 4-7 keys, 1.0e-2 with 8-15, 9e-3 with 16-63, 5.5e-3 with 64-95;
+#   rotated keys only (which the bf16 cache makes unavoidable): 7.9e-3 at worst, in every class.
+# Rows with fewer than 64 keys therefore never reach the matrix kernel: the library serves them in
+# fp32 from the stored keys (keys-only rounding), and every row is held to the workload's bar.
+FEW_KEYS = 64
 
 
 def check_rows(got, want, keys_seen, what):
-    """keys_seen[i]: number of keys row i attends to."""
+    """keys_seen[i]: number of keys row i attends to.  One bar for all rows, checked over all of
+    them and once more over the rows with few keys alone (a class that the many long rows of a
+    case would otherwise hide in the mean)."""
     from harness import check_close
-    many = keys_seen >= FEW_KEYS
-    if many.any():
-        check_close(got[many], want[many], MAX_ABS, MEAN_ABS, what)
-    if (~many).any():
-        check_close(got[~many], want[~many], MAX_ABS_FEW, MEAN_ABS_FEW, what + " (rows with few keys)")
+    check_close(got, want, MAX_ABS, MEAN_ABS, what)
+    few = keys_seen < FEW_KEYS
+    if few.any():
+        check_close(got[few], want[few], MAX_ABS, MEAN_ABS, what + " (rows with few keys)")
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -152,7 +154,10 @@ def operand_rounded_reference(shape, chunks, step, pos0):
     k_all = np.concatenate([c[1] for c in chunks[:step + 1]], axis=0)
     v_all = np.concatenate([c[2] for c in chunks[:step + 1]], axis=0).astype(np.float64)
     k_rot = bf16(oracle.rope(k_all, pos0 + np.arange(C + n), shape.rope_base))
-    q_rot = bf16(oracle.rope(q, pos0 + C + np.arange(n), shape.rope_base) * (np.log2(np.e) / np.sqrt(d)))
+    q_rot = oracle.rope(q, pos0 + C + np.arange(n), shape.rope_base) * (np.log2(np.e) / np.sqrt(d))
+    # (rows with fewer than 64 keys are served in fp32: their queries are not rounded)
+    matrix_rows = C + 1 + np.arange(n) >= FEW_KEYS
+    q_rot[matrix_rows] = bf16(q_rot[matrix_rows])
     visible = np.arange(C + n)[None, :] <= (C + np.arange(n))[:, None]
     out = np.empty((n, shape.n_q_heads, d))
     for h in range(shape.n_q_heads):
@@ -168,7 +173,8 @@ def test_random_episode_against_the_operand_rounded_reference(seed):
     """The plain steps of the random episodes once more, against the reference above: without the
     operands' rounding noise in the way the path has to be closer, at every row -- by what the
     remaining roundings allow (over 300 seeds: 2.6e-3 / 2.1e-4 at worst on rows with 64 or more
-    keys, 4.5e-3 / 4.6e-4 on rows with fewer)."""
+    keys; rows with fewer are computed in fp32 and differ from the reference only where the
+    rotation of a key in float lands on the other side of a bf16 rounding boundary)."""
     from harness import GpuLayer, check_close
     rng, shape, lens, pos0, workspace = draw_case(seed)
     layer = GpuLayer(shape, [sum(lens)], random_pages=bool(seed % 2), out_f32=True)
@@ -186,4 +192,4 @@ def test_random_episode_against_the_operand_rounded_reference(seed):
         if many.any():
             check_close(got[many], want[many], 4e-3, 3.5e-4, what)
         if (~many).any():
-            check_close(got[~many], want[~many], 7e-3, 7e-4, what + " (rows with few keys)")
+            check_close(got[~many], want[~many], 2e-3, 1e-4, what + " (rows with few keys)")
