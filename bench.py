@@ -29,8 +29,21 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes one attention launch of the workload below moves, from two rocprofv3 --pmc passes
 # (FETCH_SIZE, WRITE_SIZE) over this very command, each scaled by what the same counter reads
 # for a 256 MiB device copy (fetch x2.000, write x1.000); summary and commands in
-# profiles/attn_layer7b_step32_6580cached_204new.txt.  Re-measure when the kernel changes.
+# profiles/attn_layer7b_step32_6580cached_204new.txt.  The figure belongs to one state of the
+# kernel source: it is stamped with that file's SHA-1, and the bench line says "traffic_stale"
+# when the source has changed since.  Beside it the line carries the bytes the launch must move
+# by construction ("traffic_modelled": K and V once, the queries once per piece of the key
+# range, the partial rows of every piece), which cannot go stale.
 ATTN_TRAFFIC_BYTES_PER_LAUNCH = 41.35e6
+ATTN_TRAFFIC_MEASURED_ON_SHA1 = "unrecorded"
+KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_10310_amd", "csrc",
+                             "evl_kernels.hip")
+
+
+def kernel_source_sha1():
+    import hashlib
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha1(f.read()).hexdigest()
 
 
 def attention_flops(Hq, d, C, n):
@@ -191,12 +204,49 @@ def main():
                 "frac_of_achievable": round(achieved_tflops / achievable_mfma, 4),
                 "achievable_peak_source": achievable_src,
                 "traffic": ATTN_TRAFFIC_BYTES_PER_LAUNCH,
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size, on kernel "
+                                  "source " + ATTN_TRAFFIC_MEASURED_ON_SHA1[:12],
+                "traffic_stale": ATTN_TRAFFIC_MEASURED_ON_SHA1 != kernel_source_sha1(),
+                # by construction: K and V once per KV head, the queries once per piece of the key range, and
+                # the partial rows (d outputs + 2 floats) of every piece written; the merge kernel's reads
+                # and the final output are the next launch's
+                "traffic_modelled": float(2 * (C + n) * Hkv * d * 2 + plan[1] * n * Hq * d * 2 +
+                                          (plan[1] * n * Hq * (d * 2 + 8) if plan[1] > 1 else n * Hq * d * 2)),
                 "flops_per_launch": flops, "avg_launch_us": round(k_avg_ms * 1e3, 2),
                 "p50_launch_us": round(float(np.median(kernel_ms)) * 1e3, 2),
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "achieved_hbm_GBps": round(alg_bytes / (k_avg_ms * 1e-3) / 1e9, 1),
                 "workgroups": plan[0], "key_splits": plan[1],
                 "ms_per_step_with_kernel_events": round((t3 - t2) * 1e3 / args.steps, 5)}
+
+    # ---------------- RoPE + append alone (HBM bound): the step's chunk and a whole-window prefill ----------------
+    def append_leg(cache_, k_, v_, C_, m_, calls=10, reps=30):
+        """p50 time of one evl_rope_append of m_ tokens behind C_ cached ones (several calls per event pair)."""
+        def many():
+            for _ in range(calls):
+                cache_.truncate(C_)
+                cache_.rope_append(k_, v_, C_, m_)
+        for _ in range(3):
+            many()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a_, b_ in evs:
+            a_.record(stream)
+            many()
+            b_.record(stream)
+        torch.cuda.synchronize()
+        us = float(np.median([a_.elapsed_time(b_) for a_, b_ in evs])) / calls * 1e3
+        nbytes = 2 * (2 * m_ * Hkv * d * 2)        # K and V read, K and V written
+        return {"n_new": m_, "cached_tokens": C_, "us_per_call": round(us, 2), "algorithmic_bytes": nbytes,
+                "GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
+                "frac_of_measured_copy": round(nbytes / us / 1e3 / achievable_copy, 4)}
+
+    rope_legs = [append_leg(cache, k_new, v_new, C, n)]
+    Wp = shape.prefix + 16 * n
+    layers_p, keep_p = make_layers(1, Wp, 16)
+    kp_, vp_ = randn_bf16(Wp, Hkv, d), randn_bf16(Wp, Hkv, d)
+    rope_legs.append(append_leg(layers_p[0][0], kp_, vp_, 0, Wp))
+    del layers_p, keep_p, kp_, vp_
 
     result = {
         "metric": "new-frame tokens/sec in chunk attention; p50 per-step latency at 20k cache",
@@ -208,6 +258,11 @@ def main():
                                "16-token pages in random order; step = rope_append + chunk_attention",
                    "cache_len": C, "n_new": n, "page_size": PAGE},
         "roofline": roofline,
+        "rope_append": {"bound": "hbm", "kernel": "rope_append_kernel<128>", "peak_GBps": PEAK_HBM_GBS,
+                        "what": "evl_rope_append alone, back-to-back calls on one stream (time per call, launch "
+                                "included); bytes = K and V of the chunk read + written; the 204-token chunk of "
+                                "the step and the 3520-token window of the re-prefill",
+                        "legs": rope_legs},
         "achievable": {"mfma_bf16_TFLOPs": achievable_mfma, "hbm_copy_GBps": achievable_copy,
                        "source": achievable_src,
                        "what": "register-resident v_mfma_f32_32x32x16_bf16 loop, constant operands, about 9 ms; "
