@@ -97,6 +97,22 @@ def build_peak_probe(verbose: bool = False) -> str:
     return out
 
 
+def build_lds_probe(verbose: bool = False) -> str:
+    """Measurement helper, a program of its own: csrc/lds_patterns_probe.hip (the LDS access patterns of
+    the attention kernel, one kernel per pattern, for a bank-conflict counter pass)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(PKG, "lds_patterns_probe")
+    cmd = [hipcc, "-x", "hip", "-O3", "-std=c++17", "--offload-arch=gfx950", "-Wno-unused-value",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", os.path.join(CSRC, "lds_patterns_probe.hip"), "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the LDS probe failed:\n" + r.stdout)
+    return out
+
+
 def build_c_abi_test(verbose: bool = False) -> str:
     """Test infrastructure: tests/c_abi/closed_forms.c, a plain C99 program that uses the library
     without Python (gcc; links libevl.so and the HIP runtime for hipMalloc / hipMemcpy)."""

@@ -337,7 +337,7 @@ static void init_params(const evl_cache *c, const void *q_new, void *out, void *
     p->max_pages_per_seq = c->d.max_pages_per_seq;
     p->out_f32 = c->d.out_dtype == EVL_OUT_F32;
     // cos/sin table: the tokens of 256 packed rows, if that stays within 48 KB of LDS
-    p->tab_tokens = std::min(MT / G + 2, (48 * 1024) / ((D / 2) * 8));
+    p->tab_tokens = std::min(MT / G + 2, (48 * 1024) / (evl::attention_tab_stride(D) * 8));
     p->q_scale = (float)(1.4426950408889634 / std::sqrt((double)D));
     std::memcpy(p->rev_freq, c->rev_freq, sizeof(p->rev_freq));
     cp->part_o = part_o;

@@ -120,8 +120,13 @@ __host__ __device__ inline int xcd_chunks_per_group(int m_tiles) {
 // Dynamic LDS bytes the attention kernel needs: the tile ring, then a region that first holds
 // the cos/sin table of the prologue (tab_tokens tokens) and, in launches whose work-groups walk
 // through several entries, afterwards the rounding residuals of the rotated queries.
+// A token's row of the table is head_dim / 2 (cos, sin) pairs plus kTabPad pairs of padding: the
+// lanes of a wave read the rows of five or six different tokens at once, and rows a multiple of
+// 256 bytes apart would all start in the same LDS bank.
+constexpr int kTabPad = 2;
+constexpr int attention_tab_stride(int head_dim) { return head_dim / 2 + kTabPad; }
 inline size_t attention_lds_bytes(int head_dim, int tab_tokens, bool multi_entry) {
-    const size_t tab = (size_t)tab_tokens * (head_dim / 2) * 2 * sizeof(float);
+    const size_t tab = (size_t)tab_tokens * attention_tab_stride(head_dim) * 2 * sizeof(float);
     const size_t residuals = multi_entry ? (size_t)kAttnRows * head_dim * 2 : 0;
     return (size_t)kAttnStages * attention_stage_bytes(head_dim) + (tab > residuals ? tab : residuals);
 }

@@ -815,8 +815,10 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     if (use_tab) {
         const int ntok = wg_last_tok - tok_first + 1;
         for (int e = tid; e < ntok * (D / 2); e += NW * 64) {
-            const float2 cs = rope_cos_sin(q_pos0 + tok_first + e / (D / 2), my_rev_freq);
-            tab[e] = make_float2(cs.x * p.q_scale, cs.y * p.q_scale);  // the score scale rides along
+            const int tk = e / (D / 2), f = e - tk * (D / 2);
+            const float2 cs = rope_cos_sin(q_pos0 + tok_first + tk, my_rev_freq);
+            // (the score scale rides along)
+            tab[tk * attention_tab_stride(D) + f] = make_float2(cs.x * p.q_scale, cs.y * p.q_scale);
         }
     }
     // Work-groups that walk through several entries keep, per lane, the rounding residuals of
@@ -892,7 +894,7 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const int pos = q_pos0 + row_tok[qb];
-            const float2 *trow = tab + (size_t)(row_tok[qb] - tok_first) * (D / 2) + 8 * h;
+            const float2 *trow = tab + (size_t)(row_tok[qb] - tok_first) * attention_tab_stride(D) + 8 * h;
 #pragma unroll
             for (int ks = 0; ks < KS / 2; ++ks) {
                 const bf16x8 lo = Q[qb][ks], hi = Q[qb][ks + KS / 2];
