@@ -1000,9 +1000,17 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     // frequency l % (D/2) and the lanes exchange them.  The queries sit in registers as bf16;
     // to keep a chain of such shifts from piling up rounding errors, what each rounding cut off
     // is kept (as bf16, lane-private in LDS) and added back before the next shift.
+    // (The new residuals are only formed if the piece goes on to a third entry: they serve the
+    // next shift and nothing else.)
     auto shift_queries = [&]() __attribute__((always_inline)) {
         const float2 f = rope_cos_sin(entry_q_pos(cur_e + 1) - entry_q_pos(cur_e),
                                       p.rev_freq[lane & (D / 2 - 1)]);
+        bool shifts_again;
+        {
+            int kl, kh, t0, nt, sh;
+            span(cur_e + 1, kl, kh, t0, nt, sh);
+            shifts_again = cur_end + nt < n_tiles;
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -1018,13 +1026,17 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
                     const float x = a * c - b * sn, y = b * c + a * sn;
                     rlo[e] = (bf16)x;
                     rhi[e] = (bf16)y;
-                    nel[e] = (bf16)(x - (float)rlo[e]);
-                    neh[e] = (bf16)(y - (float)rhi[e]);
+                    if (shifts_again) {
+                        nel[e] = (bf16)(x - (float)rlo[e]);
+                        neh[e] = (bf16)(y - (float)rhi[e]);
+                    }
                 }
                 Q[qb][ks] = rlo;
                 Q[qb][ks + KS / 2] = rhi;
-                resid[(qb * KS + ks) * 64] = nel;
-                resid[(qb * KS + ks + KS / 2) * 64] = neh;
+                if (shifts_again) {
+                    resid[(qb * KS + ks) * 64] = nel;
+                    resid[(qb * KS + ks + KS / 2) * 64] = neh;
+                }
                 __builtin_amdgcn_sched_barrier(0);  // one slice at a time: few registers in flight
             }
     };
@@ -1340,7 +1352,14 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
                 const int r = it * RPI + lane / LPR, c = lane % LPR;
                 const long long dr = __shfl(drow, r);
                 const bf16x8 val = *(const bf16x8 *)(stg + (qb * 32 + r) * RS + c * 16);
-                if (dr >= 0) *(bf16x8 *)(base + dr * D + c * 8) = val;
+                // (partial rows are read once, by another kernel: streamed past the L2, so that the end of
+                // this kernel has less to write back; measured -0.8 us per launch at the 7B step's shape)
+                if (dr >= 0) {
+                    if (direct)
+                        *(bf16x8 *)(base + dr * D + c * 8) = val;
+                    else
+                        __builtin_nontemporal_store(val, (bf16x8 *)(base + dr * D + c * 8));
+                }
             }
         }
     }
