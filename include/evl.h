@@ -23,8 +23,18 @@
  *   - Input buffers must stay alive and unchanged until the stream has run the kernels.
  *   - An evl_cache is a small HOST object (lengths and geometry of one layer's cache).  It
  *     is not thread-safe; use one thread per cache.
- *   - All functions return EVL_OK (0) or a negative evl_status; on error nothing has been
- *     enqueued and evl_last_error() describes the problem.
+ *   - All functions return EVL_OK (0) or a negative evl_status, and evl_last_error() describes
+ *     the problem.  Every argument is checked before anything is enqueued: a call refused for
+ *     its arguments (any status but EVL_ERR_LAUNCH) has enqueued nothing and changed nothing.
+ *     EVL_ERR_LAUNCH comes from the HIP runtime in mid-call: a call that takes several launches
+ *     (more than 64 sequences, an attention call with its merge) may by then have enqueued
+ *     some of them, and an append has recorded exactly the sequences whose launch went out.
+ *   - Under HIP graph capture: calls that use the ticket counters at the end of the workspace
+ *     (chunks of a few tokens, see evl_workspace_bytes) clear them with a small kernel the
+ *     first time a cache object needs them.  Make that first call outside the capture (one
+ *     eager call on the cache does it); otherwise the clearing is only recorded and runs with
+ *     the first replay, and eager calls made before that replay would find the counters
+ *     uncleared.
  *
  * Layouts (row-major, bf16 unless stated)
  *   q_new [n][Hq][d], k_new / v_new [n][Hkv][d], out [n][Hq][d]: token-major, as a QKV
