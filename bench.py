@@ -541,6 +541,14 @@ def main():
         ms_pack = timed_ms(lambda: cP.isolated_pack_attention(qP, shape.prefix, Fv, Av, Nf, outP), 30)
         plan_pack = cP.last_plan()
         ms_causal = timed_ms(lambda: cP.chunk_attention(qP, 0, Lp, outP), 30)
+        # the same pack appended with the ids the mask implies (evl_isolated_pack_append): one causal launch
+        # in which the earlier steps' action tokens are holes of the key range
+        layersQ, keepQ = make_layers(1, Lp, 64 << 20)
+        cQ = layersQ[0][0]
+        cQ.isolated_pack_append(kP, vP, 0, shape.prefix, Fv, Av, Nf)
+        ms_pack_ids = timed_ms(lambda: cQ.isolated_pack_attention(qP, shape.prefix, Fv, Av, Nf, outP), 30)
+        plan_pack_ids = cQ.last_plan()
+        del layersQ, keepQ, cQ
         pairs = 0   # visible (query, key) pairs under the mask
         nv = shape.prefix
         pairs += shape.prefix * (shape.prefix + 1) // 2
@@ -555,6 +563,9 @@ def main():
                         "sampled call)" % Lp,
             "ms": round(ms_pack, 4), "attention_TFLOPs": round(fl_pack / (ms_pack * 1e-3) / 1e12, 1),
             "visible_pairs": pairs, "plan": plan_pack,
+            "appended_with_pack_ids_ms": round(ms_pack_ids, 4),
+            "appended_with_pack_ids_TFLOPs": round(fl_pack / (ms_pack_ids * 1e-3) / 1e12, 1),
+            "appended_with_pack_ids_plan": plan_pack_ids,
             "plain_causal_same_tokens_ms": round(ms_causal, 4)}
         del layersP, keepP, cP
 

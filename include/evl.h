@@ -237,6 +237,25 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *cac
 evl_status evl_isolated_pack_attention(const void *q_packed, evl_cache *cache, int32_t seq,
                                        int32_t prefix, int32_t frame_tokens, int32_t action_tokens,
                                        int32_t n_frames, void *out_packed);
+/*
+ * Sec. 3.3, the faster way to the same result: append the whole pack to the EMPTY sequence `seq`
+ * with the position ids the action-isolating mask implies -- instruction and visual tokens are
+ * numbered without a gap from pos0 (action tokens skipped), the action tokens of step t continue
+ * right behind frame t -- instead of the contiguous ids of evl_rope_append.  Keys are rotated at
+ * those ids and stored, values stored as given, at the sequence indices 0 .. L-1 of the pack
+ * order (L = prefix + n_frames * (frame_tokens + action_tokens)).  evl_isolated_pack_attention on
+ * such a sequence (same prefix / frame_tokens / action_tokens, any n_frames up to the appended
+ * ones) then runs as ONE causal launch in which the action tokens of earlier steps are holes of
+ * the key range: no run list, no per-run shift of the queries; results agree with the route
+ * through evl_rope_append to rounding.  Served shapes: action_tokens >= 1, frame_tokens +
+ * action_tokens >= 64, prefix >= 63 (EVL_ERR_UNSUPPORTED otherwise: use evl_rope_append).  A
+ * sequence that holds a pack takes no further appends and no other attention call until
+ * evl_cache_reset (EVL_ERR_NONCONTIGUOUS / EVL_ERR_ARG).  k_packed, v_packed: DEVICE bf16
+ * [L][Hkv][d], 16-byte aligned.
+ */
+evl_status evl_isolated_pack_append(evl_cache *cache, int32_t seq, const void *k_packed,
+                                    const void *v_packed, int64_t pos0, int32_t prefix,
+                                    int32_t frame_tokens, int32_t action_tokens, int32_t n_frames);
 /* Workspace that serves evl_chunk_attention_sampled for chunks of up to max_n_new tokens and
  * up to max_runs runs (it also serves the plain calls on one sequence). */
 size_t evl_workspace_bytes_sampled(const evl_cache_desc *desc, int32_t max_n_new,

@@ -25,7 +25,7 @@ EXPORTS = ["evl_cache_create", "evl_cache_destroy", "evl_cache_reset", "evl_cach
            "evl_chunk_attention_sampled", "evl_workspace_bytes_sampled", "evl_sample_uniform",
            "evl_sample_window", "evl_chunk_attention_sampled_batched", "evl_isolated_pack_attention",
            "evl_pages_copy", "evl_step", "evl_step_batched", "evl_step_sampled",
-           "evl_cache_launches", "evl_chunk_attention_static"]
+           "evl_cache_launches", "evl_chunk_attention_static", "evl_isolated_pack_append"]
 
 
 def status_name(code: int) -> str:
@@ -100,6 +100,7 @@ def declare(L):
     L.evl_chunk_attention_sampled_batched.argtypes = [vp, vp, i32, pi32, pi32, pi32, pi32, pi32,
                                                       C.POINTER(Run), vp]
     L.evl_isolated_pack_attention.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+    L.evl_isolated_pack_append.argtypes = [vp, i32, vp, vp, i64, i32, i32, i32, i32]
     L.evl_pages_copy.argtypes = [vp, vp, vp, pi32, i32, vp, vp, pi32, i32, i32]
     L.evl_step.argtypes = [vp, vp, vp, vp, i64, i32, vp]
     L.evl_step_sampled.argtypes = [vp, vp, vp, vp, i32, C.POINTER(Run), i32, i64, i32, vp]
@@ -277,6 +278,11 @@ class Cache:
         _check(load().evl_isolated_pack_attention(_ptr(q_packed), self._h, int(seq), int(prefix),
                                                   int(frame_tokens), int(action_tokens), int(n_frames),
                                                   _ptr(out_packed)))
+
+    def isolated_pack_append(self, k_packed, v_packed, pos0: int, prefix: int, frame_tokens: int,
+                             action_tokens: int, n_frames: int, seq: int = 0) -> None:
+        _check(load().evl_isolated_pack_append(self._h, int(seq), _ptr(k_packed), _ptr(v_packed), int(pos0),
+                                               int(prefix), int(frame_tokens), int(action_tokens), int(n_frames)))
 
     def pages_copy(self, dst_k, dst_v, dst_pages, dst_pool_pages: int, src_k, src_v, src_pages,
                    src_pool_pages: int) -> None:

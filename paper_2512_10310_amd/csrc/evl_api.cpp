@@ -39,6 +39,12 @@ struct Plan {
 
 }  // namespace
 
+// Shape of a pack under the action-isolating mask: `prefix` instruction tokens, then steps of
+// frame_tokens visual + action_tokens action tokens.  action_tokens == 0: not a pack.
+struct PackShape {
+    int32_t prefix = 0, frame_tokens = 0, action_tokens = 0;
+};
+
 struct evl_cache {
     evl_cache_desc d;
     int group;
@@ -47,6 +53,7 @@ struct evl_cache {
     double rev_freq[evl::kMaxHalfDim];  // theta_j / (2 pi)
     std::vector<int64_t> len, pos0;
     std::vector<char> has_pos0;
+    std::vector<PackShape> pack;  // per sequence: set by evl_isolated_pack_append (position ids skip action tokens)
     Plan last_plan;
     bool counters_zeroed = false;  // the ticket counters at the end of the workspace are ready
     // measurement aid: ring of event pairs around the attention kernel
@@ -103,6 +110,7 @@ evl_status evl_cache_create(const evl_cache_desc *desc, evl_cache **out) {
     c->len.assign(desc->max_seqs, 0);
     c->pos0.assign(desc->max_seqs, 0);
     c->has_pos0.assign(desc->max_seqs, 0);
+    c->pack.assign(desc->max_seqs, PackShape());
     *out = c;
     return EVL_OK;
 }
@@ -134,6 +142,7 @@ evl_status evl_cache_reset(evl_cache *cache, int32_t seq) {
     if (st != EVL_OK) return st;
     cache->len[seq] = 0;
     cache->has_pos0[seq] = 0;
+    cache->pack[seq] = PackShape();
     return EVL_OK;
 }
 
@@ -144,7 +153,10 @@ evl_status evl_cache_truncate(evl_cache *cache, int32_t seq, int32_t new_len) {
         return fail(EVL_ERR_RANGE, "truncate to %d: sequence %d holds %lld tokens", new_len, seq,
                     (long long)cache->len[seq]);
     cache->len[seq] = new_len;
-    if (new_len == 0) cache->has_pos0[seq] = 0;
+    if (new_len == 0) {
+        cache->has_pos0[seq] = 0;
+        cache->pack[seq] = PackShape();
+    }
     return EVL_OK;
 }
 
@@ -205,6 +217,10 @@ static evl_status check_append(evl_cache *c, const void *k_new, const void *v_ne
         if (n_new[i] <= 0) return fail(EVL_ERR_ARG, "n_new[%d] = %d must be positive", i, n_new[i]);
         if (pos_offsets[i] < 0 || pos_offsets[i] + n_new[i] > (int64_t)INT32_MAX)
             return fail(EVL_ERR_ARG, "position ids of entry %d leave [0, 2^31)", i);
+        if (c->pack[s].action_tokens > 0)
+            return fail(EVL_ERR_NONCONTIGUOUS,
+                        "sequence %d holds a pack (evl_isolated_pack_append), whose position ids skip action "
+                        "tokens: reset it before appending", s);
         if (c->has_pos0[s] && pos_offsets[i] != c->pos0[s] + c->len[s])
             return fail(EVL_ERR_NONCONTIGUOUS,
                         "sequence %d: pos_offset %lld does not continue the cache (expected %lld)",
@@ -636,7 +652,8 @@ static evl_status decode_attention(evl_cache *c, const void *q_new, void *out,
 
 static evl_status attention_batched_core(const void *q_new, evl_cache *c, const int32_t *seq_ids,
                                          const int32_t *cache_lens, const int32_t *n_new, const int32_t *tok_offs_in,
-                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few);
+                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few,
+                                         const PackShape *pack = nullptr);
 
 evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const int32_t *seq_ids,
                                        const int32_t *cache_lens, const int32_t *n_new,
@@ -655,6 +672,8 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
         if (st != EVL_OK) return st;
         if (seen[s]) return fail(EVL_ERR_ARG, "sequence %d listed twice", s);
         seen[s] = 1;
+        if (c->pack[s].action_tokens > 0)
+            return fail(EVL_ERR_ARG, "sequence %d holds a pack: use evl_isolated_pack_attention", s);
         if (n_new[i] <= 0) return fail(EVL_ERR_ARG, "n_new[%d] = %d must be positive", i, n_new[i]);
         if (cache_lens[i] < 0) return fail(EVL_ERR_ARG, "cache_lens[%d] is negative", i);
         if ((int64_t)cache_lens[i] + n_new[i] > c->len[s])
@@ -694,13 +713,14 @@ evl_status evl_chunk_attention_batched(const void *q_new, evl_cache *c, const in
 // off, which travel with the first attention launch(es) or, behind the decode kernel, alone.
 static evl_status attention_batched_core(const void *q_new, evl_cache *c, const int32_t *seq_ids,
                                          const int32_t *cache_lens, const int32_t *n_new, const int32_t *tok_offs_in,
-                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few) {
+                                         int32_t n_seqs, void *out, const std::vector<FewGroup> &few,
+                                         const PackShape *pack) {
     const int D = c->d.head_dim, Hq = c->d.n_q_heads, Hkv = c->d.n_kv_heads, G = c->group;
     const int MT = evl::attention_rows_per_workgroup();
     const int KN = evl::kKeyTile;
 
-    // chunks of a few tokens everywhere: the decode kernel
-    {
+    // chunks of a few tokens everywhere: the decode kernel (which knows nothing of packs)
+    if (!pack) {
         std::vector<DecodeEntry> ents(n_seqs);
         std::vector<int> first(n_seqs + 1);
         for (int i = 0; i < n_seqs; ++i) {
@@ -802,6 +822,11 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
         evl::CombineParams cp;
         init_params(c, q_new, out, part_o, part_ml, &p, &cp);
         p.n_seqs = cnt;
+        if (pack) {
+            p.hole_first = pack->prefix;
+            p.hole_period = pack->frame_tokens + pack->action_tokens;
+            p.hole_width = pack->action_tokens;
+        }
         attach_few(c, &p, few, &few_next);
         int items = 0, crow = 0, cseqs = 0;
         int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -968,6 +993,8 @@ static evl_status build_entries(const evl_cache *c, int32_t seq, const evl_run *
     if (n_runs < 0 || (n_runs > 0 && !runs)) return fail(EVL_ERR_NULL, "runs is NULL");
     evl_status st = check_seq(c, seq);
     if (st != EVL_OK) return st;
+    if (c->pack[seq].action_tokens > 0)
+        return fail(EVL_ERR_ARG, "sequence %d holds a pack: use evl_isolated_pack_attention", seq);
     if (n_new <= 0) return fail(EVL_ERR_ARG, "n_new = %d must be positive", n_new);
     if (cache_len < 0) return fail(EVL_ERR_ARG, "cache_len is negative");
     if (appended && (int64_t)cache_len + n_new > c->len[seq])
@@ -1412,6 +1439,47 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
 // (a frame's visual tokens followed by its action tokens) are groups of the batched sampled
 // call, whose runs are what the mask lets the step see; the contiguous ids over those runs are
 // the ids the corresponding single-step example would have.
+// Appends a whole pack to an empty sequence with the position ids of the action-isolating mask:
+// instruction and visual tokens are numbered without a gap, the action tokens of a step continue
+// behind their frame, so that a later attention call needs no per-run shift of its queries.
+evl_status evl_isolated_pack_append(evl_cache *c, int32_t seq, const void *k_packed, const void *v_packed,
+                                    int64_t pos0, int32_t prefix, int32_t frame_tokens, int32_t action_tokens,
+                                    int32_t n_frames) {
+    if (!c) return fail(EVL_ERR_NULL, "cache is NULL");
+    if (prefix < 0 || frame_tokens <= 0 || action_tokens < 0 || n_frames < 0 || (prefix == 0 && n_frames == 0))
+        return fail(EVL_ERR_ARG, "bad pack shape: prefix %d, %d frames of %d + %d tokens", prefix, n_frames,
+                    frame_tokens, action_tokens);
+    const int64_t step = (int64_t)frame_tokens + action_tokens, total = (int64_t)prefix + n_frames * step;
+    if (total > INT32_MAX / 2) return fail(EVL_ERR_ARG, "pack too long");
+    if (action_tokens < 1 || step < evl::kKeyTile || prefix < evl::kFewKeys - 1)
+        return fail(EVL_ERR_UNSUPPORTED,
+                    "evl_isolated_pack_append serves packs with action tokens, at least %d tokens per step and an "
+                    "instruction of at least %d tokens (got %d + %d, %d): append with evl_rope_append instead",
+                    evl::kKeyTile, evl::kFewKeys - 1, frame_tokens, action_tokens, prefix);
+    evl_status st = check_seq(c, seq);
+    if (st != EVL_OK) return st;
+    if (c->len[seq] != 0)
+        return fail(EVL_ERR_NONCONTIGUOUS, "sequence %d holds %lld tokens: a pack goes into an empty sequence", seq,
+                    (long long)c->len[seq]);
+    const int32_t n_new = (int32_t)total;
+    st = check_append(c, k_packed, v_packed, &seq, &pos0, &n_new, 1);
+    if (st != EVL_OK) return st;
+    evl::AppendParams p;
+    int64_t tok_off = 0;
+    fill_append(c, k_packed, v_packed, &seq, &pos0, &n_new, 0, 1, &tok_off, &p);
+    p.hole_first = prefix;
+    p.hole_period = (int32_t)step;
+    p.hole_width = action_tokens;
+    hipError_t e = evl::launch_rope_append(p, c->d.head_dim, (hipStream_t)c->d.stream);
+    if (e == hipSuccess) ++c->n_launches;
+    if (e != hipSuccess) return fail(EVL_ERR_LAUNCH, "rope_append launch failed: %s", hipGetErrorString(e));
+    commit_append(c, &seq, &pos0, &n_new, 0, 1);
+    c->pack[seq].prefix = prefix;
+    c->pack[seq].frame_tokens = frame_tokens;
+    c->pack[seq].action_tokens = action_tokens;
+    return EVL_OK;
+}
+
 evl_status evl_isolated_pack_attention(const void *q_packed, evl_cache *c, int32_t seq, int32_t prefix,
                                        int32_t frame_tokens, int32_t action_tokens, int32_t n_frames,
                                        void *out_packed) {
@@ -1422,6 +1490,31 @@ evl_status evl_isolated_pack_attention(const void *q_packed, evl_cache *c, int32
                     frame_tokens, action_tokens);
     const int64_t step = (int64_t)frame_tokens + action_tokens;
     if ((int64_t)prefix + n_frames * step > INT32_MAX / 2) return fail(EVL_ERR_ARG, "pack too long");
+    // A sequence appended with the pack's own ids: one causal launch in which the action tokens of
+    // earlier steps are holes of the key range; no run list, no shifted queries.
+    if (check_seq(c, seq) == EVL_OK && c->pack[seq].action_tokens > 0) {
+        const PackShape &ps = c->pack[seq];
+        if (ps.prefix != prefix || ps.frame_tokens != frame_tokens || ps.action_tokens != action_tokens)
+            return fail(EVL_ERR_ARG, "sequence %d holds a pack of shape %d + n x (%d + %d), asked for %d + n x (%d + %d)",
+                        seq, ps.prefix, ps.frame_tokens, ps.action_tokens, prefix, frame_tokens, action_tokens);
+        if (!q_packed || !out_packed) return fail(EVL_ERR_NULL, "q_packed / out_packed is NULL");
+        if (!aligned16(q_packed) || !aligned16(out_packed))
+            return fail(EVL_ERR_ALIGN, "q_packed / out_packed must be 16-byte aligned");
+        const int64_t total = (int64_t)prefix + n_frames * step;
+        if (total > c->len[seq])
+            return fail(EVL_ERR_RANGE, "sequence %d: the pack has %lld tokens, %lld were appended", seq,
+                        (long long)total, (long long)c->len[seq]);
+        // the first 63 tokens (inside the instruction: prefix >= 63) see fewer than 64 keys
+        const int32_t a = (int32_t)std::min<int64_t>(evl::kFewKeys - 1, total);
+        std::vector<FewGroup> few;
+        few.push_back(FewGroup{seq, 0, a, 0, {Entry{0, a, 1, c->pos0[seq], 0}}});
+        if (total == a) {
+            c->last_plan = Plan();
+            return few_keys_attention(c, q_packed, out_packed, few);
+        }
+        const int32_t rest = (int32_t)(total - a);
+        return attention_batched_core(q_packed, c, &seq, &a, &rest, &a, 1, out_packed, few, &ps);
+    }
     std::vector<int32_t> seqs, lens, ns, toks, offs(1, 0);
     std::vector<evl_run> runs;
     auto add_group = [&](int32_t begin, int32_t n, int frames_visible) {

@@ -31,6 +31,11 @@ struct AppendParams {
     const int32_t *block_table;
     int32_t *pos_tags;   // may be null
     int32_t n_kv_heads, n_pages, max_pages_per_seq, n_seqs, n_items, pad_;
+    // Packed sequence under the action-isolating mask (hole_width > 0; one sequence per launch):
+    // the token at sequence index t belongs to step s(t) = (t - hole_first) / hole_period (0 before
+    // hole_first), the last hole_width tokens of every step are that step's action tokens, and
+    // position ids skip the action tokens of earlier steps: id(t) = pos_begin + t - hole_width * s(t).
+    int32_t hole_first, hole_period, hole_width, pad2_;
     double rev_freq[kMaxHalfDim];  // theta_j / (2 pi): turns per position
     AppendSeq seq[kMaxSeqs];
 };
@@ -82,6 +87,11 @@ struct AttnParams {
     // few_entries), few_rows (token, query head) rows in all.  In an attention launch they ride
     // along as extra work-groups behind the 8 * items_per_xcd of the matrix part.
     int32_t few_first, few_entries, few_rows;
+    // Packed sequence under the action-isolating mask (hole_width > 0; the launch serves one
+    // sequence, plain build): steps and position ids as in AppendParams; the action tokens of a step
+    // are visible to the rows of that step only (a "hole" in what later steps see).  The kernel
+    // handles at most two holes per key tile: hole_period >= kKeyTile.
+    int32_t hole_first, hole_period, hole_width;
     double rev_freq[kMaxHalfDim];  // theta_j / (2 pi): turns per position
     AttnSeq seq[kMaxEntries];
 };

@@ -307,7 +307,12 @@ __device__ __forceinline__ void rope_append_body(const AppendParams &p, const in
         const int t = k_t;
         if (k_mine) {
             const int i = t - sq.t_begin;
-            const int pos = (int)sq.pos_begin + i;
+            int pos = (int)sq.pos_begin + i;
+            if (p.hole_width > 0) {  // a pack: ids skip the action tokens of earlier steps
+                const int st = t < p.hole_first ? 0 : (t - p.hole_first) / p.hole_period;
+                const int s0 = sq.t_begin < p.hole_first ? 0 : (sq.t_begin - p.hole_first) / p.hole_period;
+                pos -= p.hole_width * (st - s0);
+            }
             const bf16x8 lo = k_lo, hi = k_hi;
             bf16x8 rlo, rhi;
 #pragma unroll
@@ -571,8 +576,10 @@ __device__ __forceinline__ void wait_loads() {
 
 // MULTI: built for groups of several entries (the sampled call); the plain build has one
 // entry per group and none of the entry-to-entry machinery.
-template <int D, int QB, bool MULTI>
+// HOLES: the sequence is a pack under the action-isolating mask (see AttnParams::hole_*).
+template <int D, int QB, bool MULTI, bool HOLES = false>
 __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kernel(const AttnParams p) {
+    static_assert(!(MULTI && HOLES), "a pack is one causal key range");
     using T = Tile<D>;
     constexpr int KN = T::KN;
     constexpr int KS = D / 16;   // k-steps of the score contraction
@@ -665,6 +672,16 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     const int R = sq.n_new * G;  // packed rows of this sequence
     const int C = sq.cache_len;
     const int row0 = mt * MT;
+    // Pack (HOLES): step of a sequence index, and the id offset of chunk token `tok` from the
+    // chunk's first token (ids skip the action tokens of the steps in between).
+    const int h_first = HOLES ? p.hole_first : 0, h_period = HOLES ? p.hole_period : 1;
+    const int h_width = HOLES ? p.hole_width : 0;
+    auto step_of = [&](int t) __attribute__((always_inline)) -> int {
+        return t < h_first ? 0 : (t - h_first) / h_period;
+    };
+    auto chunk_pos = [&](int tok) __attribute__((always_inline)) -> int {
+        return HOLES ? tok - h_width * (step_of(C + tok) - step_of(C)) : tok;
+    };
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
@@ -816,7 +833,7 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
         const int ntok = wg_last_tok - tok_first + 1;
         for (int e = tid; e < ntok * (D / 2); e += NW * 64) {
             const int tk = e / (D / 2), f = e - tk * (D / 2);
-            const float2 cs = rope_cos_sin(q_pos0 + tok_first + tk, my_rev_freq);
+            const float2 cs = rope_cos_sin(q_pos0 + chunk_pos(tok_first + tk), my_rev_freq);
             // (the score scale rides along)
             tab[tk * attention_tab_stride(D) + f] = make_float2(cs.x * p.q_scale, cs.y * p.q_scale);
         }
@@ -893,7 +910,7 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
         if (use_tab) __syncthreads();
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const int pos = q_pos0 + row_tok[qb];
+            const int pos = q_pos0 + chunk_pos(row_tok[qb]);
             const float2 *trow = tab + (size_t)(row_tok[qb] - tok_first) * attention_tab_stride(D) + 8 * h;
 #pragma unroll
             for (int ks = 0; ks < KS / 2; ++ks) {
@@ -1074,7 +1091,52 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
             P[qb][kb][v >> 3][(v & 7) + 1] = e[1];
         }
     };
+    // Pack (HOLES): hole_lo / hole_step follow the tiles as the loop advances -- the first hole
+    // (a step's action tokens) that ends behind the current tile's first key, and its step.  With
+    // hole_period >= KN a tile meets at most that hole and the next one.  A hole is hidden from the
+    // rows of later steps only.
+    int hole_lo = 0, hole_step = 0, row_step[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) row_step[qb] = HOLES ? step_of(C + row_tok[qb]) : 0;
+    auto seek_hole = [&](int t) __attribute__((always_inline)) -> bool {  // true: tile t meets a hole
+        const int k0 = t * KN + cur_sh;
+        while (hole_lo + h_width <= k0) {
+            hole_lo += h_period;
+            ++hole_step;
+        }
+        return hole_lo < k0 + KN;
+    };
+    // bits [lo, lo + w) of a 64-bit word, clipped to the word
+    auto bit_range = [](int lo, int w) __attribute__((always_inline)) -> unsigned long long {
+        const int a = max(lo, 0), b = min(lo + w, 64);
+        if (b <= a) return 0ull;
+        return (b - a >= 64 ? ~0ull : (1ull << (b - a)) - 1ull) << a;
+    };
     auto apply_mask = [&](f32x16 (&S_cur)[QB][2], int t) __attribute__((always_inline)) {
+        if (HOLES) {
+            // A pack masks about every third tile: the hidden keys of the tile are gathered in a 64-bit
+            // word per row (bit x = key x of the tile) -- the two holes (wave-uniform words, dropped for
+            // rows of the hole's own step or an earlier one), the causal limit, the range's lower end --
+            // and every score then costs one bit test.
+            const int k0 = t * KN + cur_sh;
+            const unsigned long long hole_a = bit_range(hole_lo - k0, h_width);
+            const unsigned long long hole_b = bit_range(hole_lo + h_period - k0, h_width);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                unsigned long long hidden = (hole_step < row_step[qb] ? hole_a : 0ull) |
+                                            (hole_step + 1 < row_step[qb] ? hole_b : 0ull);
+                hidden |= ~bit_range(0, klim[qb] - k0);   // keys at or past the row's limit
+                hidden |= bit_range(0, cur_k_lo - k0);    // keys before the range
+                // this lane's keys are 32 kb + 16 (v / 8) + 8 h + v % 8
+                const unsigned w[2] = {(unsigned)hidden >> (8 * h), (unsigned)(hidden >> 32) >> (8 * h)};
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if ((w[kb] >> (16 * (v >> 3) + (v & 7))) & 1u) S_cur[qb][kb][v] = -INFINITY;
+            }
+            return;
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const int lim = klim[qb] - t * KN - cur_sh - 8 * h;  // local key index bounds for this lane
@@ -1272,7 +1334,27 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
                 for (int kb = 0; kb < 2; ++kb) SA[qb][kb] = SB[qb][kb];
         };
         int i = 0;
-        if (!multi) {
+        if (HOLES) {
+            // a pack: tiles that meet a hole are scattered over the key range
+            {   // the first hole that can matter for this piece's first tile
+                const int k0 = cur_off * KN + cur_sh;
+                hole_step = step_of(max(k0, h_first));
+                hole_lo = h_first + hole_step * h_period + (h_period - h_width);
+            }
+            for (; i + 2 < n_tiles; i += 2) {  // two per round: the score buffers swap roles without copies
+                const bool hole0 = seek_hole(i + cur_off);
+                iteration(i, needs_mask(i) || hole0, no(), SA, SB);
+                const bool hole1 = seek_hole(i + 1 + cur_off);
+                iteration(i + 1, needs_mask(i + 1) || hole1, no(), SB, SA);
+            }
+            for (; i < n_tiles - 1; ++i) {
+                const bool hole = seek_hole(i + cur_off);
+                iteration(i, needs_mask(i) || hole, no(), SA, SB);
+                to_a();
+            }
+            const bool hole = seek_hole(i + cur_off);
+            iteration(i, needs_mask(i) || hole, yes(), SA, SB);
+        } else if (!multi) {
             // one entry: the tiles that need a mask are the first (if the entry starts inside
             // it) and the last few; the fully visible ones in between get a loop of their own
             const int i_mask = t_mask - cur_off;
@@ -2013,26 +2095,32 @@ static hipError_t allow_large_lds(const void *fn, LargeLdsOnce &st) {
 
 // ev_start / ev_stop (both or neither): events the runtime stamps with the begin and the end of
 // this very dispatch (not of the stream around it).
-template <int D, int QB, bool MULTI>
+template <int D, int QB, bool MULTI, bool HOLES = false>
 static hipError_t launch_attn(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     const size_t lds = attention_lds_bytes(D, p.tab_tokens, MULTI);
     static LargeLdsOnce large_lds;
     if (lds > 64 * 1024) {
-        hipError_t e = allow_large_lds((const void *)attn_kernel<D, QB, MULTI>, large_lds);
+        hipError_t e = allow_large_lds((const void *)attn_kernel<D, QB, MULTI, HOLES>, large_lds);
         if (e != hipSuccess) return e;
     }
     constexpr int NW = kRowsPerWorkgroup / (32 * QB);
     const dim3 grid(p.items_per_xcd * 8 + (p.few_rows + NW - 1) / NW), block(NW * 64);
     if (ev_start)
-        hipExtLaunchKernelGGL((attn_kernel<D, QB, MULTI>), grid, block, (uint32_t)lds, stream, ev_start, ev_stop, 0, p);
+        hipExtLaunchKernelGGL((attn_kernel<D, QB, MULTI, HOLES>), grid, block, (uint32_t)lds, stream, ev_start, ev_stop, 0, p);
     else
-        hipLaunchKernelGGL((attn_kernel<D, QB, MULTI>), grid, block, lds, stream, p);
+        hipLaunchKernelGGL((attn_kernel<D, QB, MULTI, HOLES>), grid, block, lds, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_chunk_attention(const AttnParams &p, int head_dim, hipStream_t stream, hipEvent_t ev_start,
                                   hipEvent_t ev_stop) {
     if (p.n_items <= 0 && p.few_rows <= 0) return hipSuccess;
+    if (p.hole_width > 0) {  // a pack under the action-isolating mask
+        if (p.multi_entry || p.hole_period < kKeyTile) return hipErrorInvalidValue;
+        if (head_dim == 128) return launch_attn<128, 1, false, true>(p, stream, ev_start, ev_stop);
+        if (head_dim == 64) return launch_attn<64, 1, false, true>(p, stream, ev_start, ev_stop);
+        return hipErrorInvalidValue;
+    }
     if (head_dim == 128)
         return p.multi_entry ? launch_attn<128, 1, true>(p, stream, ev_start, ev_stop)
                              : launch_attn<128, 1, false>(p, stream, ev_start, ev_stop);

@@ -168,6 +168,20 @@ def episode(probe, seed):
                 continue
             call("isolated_pack_attention (%d + %d x (%d + %d))" % (prefix, frames, ft, at),
                  lambda: c.isolated_pack_attention(Q, prefix, ft, at, frames, OUT, seq=s))
+            # the same pack appended with its own position ids: one causal launch with holes
+            if prefix >= 63 and ft + at >= 64 and at >= 1 and frames >= 1 and rng.integers(0, 2):
+                free = [x for x in range(max_seqs) if lens[x] == 0]
+                total = prefix + frames * (ft + at)
+                if free and total <= cap_tokens:
+                    x = free[0]
+                    p0 = int(rng.choice([0, 5, 40000]))
+                    call("isolated_pack_append", lambda: c.isolated_pack_append(K, V, p0, prefix, ft, at, frames, seq=x))
+                    lens[x], pos0[x] = total, p0
+                    fewer = int(rng.integers(0, frames + 1))
+                    call("isolated_pack_attention on a pack (%d of %d frames)" % (fewer, frames),
+                         lambda: c.isolated_pack_attention(Q, prefix, ft, at, fewer, OUT, seq=x))
+                    call("reset", lambda: c.reset(x))
+                    lens[x], pos0[x] = 0, None
         elif op in (7, 8):                            # append and attend in one call
             ss = some_seqs(False)
             short = bool(rng.integers(0, 2))

@@ -127,6 +127,11 @@ hipError_t launch_rope_append(const AppendParams &p, int head_dim, hipStream_t) 
         tok += q.n_new;
     }
     REQUIRE(p.n_items == items, "%s: n_items %d, the sequences touch %d (page, head) pairs", who, p.n_items, items);
+    if (p.hole_width != 0)  // a pack: one sequence, from its first token, steps no shorter than their action tokens
+        REQUIRE(p.n_seqs == 1 && p.seq[0].t_begin == 0 && p.hole_width > 0 && p.hole_first >= 0 &&
+                    p.hole_period > p.hole_width,
+                "%s: pack of %d sequences from token %d, steps of %d with %d action tokens after %d", who, p.n_seqs,
+                p.seq[0].t_begin, p.hole_period, p.hole_width, p.hole_first);
     return hipSuccess;
 }
 
@@ -213,6 +218,12 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
     REQUIRE(p.n_items == items, "%s: n_items %d, entries describe %d", who, p.n_items, items);
     REQUIRE(p.items_per_xcd == *std::max_element(per_xcd, per_xcd + 8), "%s: items_per_xcd %d, fullest XCD has %d",
             who, p.items_per_xcd, *std::max_element(per_xcd, per_xcd + 8));
+    if (p.hole_width != 0) {  // a pack: one causal key range, at most two holes per key tile, rows of a few keys inside the instruction
+        REQUIRE(p.hole_width > 0 && p.hole_period >= KN && p.hole_period > p.hole_width && p.hole_first >= kFewKeys - 1,
+                "%s: pack with steps of %d tokens, %d of them action tokens, after %d", who, p.hole_period, p.hole_width,
+                p.hole_first);
+        REQUIRE(!multi && !p.multi_entry && p.n_seqs == 1 && p.seq[0].k_begin == 0, "%s: a pack is one causal key range", who);
+    }
     // (the multi-entry build also serves groups of one entry; the plain build serves nothing else)
     REQUIRE(p.multi_entry || !multi, "%s: groups of several entries given to the plain build", who);
     // (a work-group whose tokens outnumber the table computes its rotations without it)

@@ -99,3 +99,75 @@ def test_isolated_pack_paper_size():
         check_close(got[head:], want[head:], MAX_ABS, MEAN_ABS, "pack, out_f32=%s" % out_f32)
         assert np.all(np.isfinite(got))
     print("plan:", layer.cache.last_plan())
+
+
+@pytest.mark.parametrize("dims,heads,pos0", [
+    ((256, 196, 8, 16), (28, 4, 128), 0),        # the paper's pack
+    ((63, 60, 4, 9), (28, 4, 128), 11),          # the smallest served shape: steps of 64 tokens, instruction of 63
+    ((100, 64, 1, 5), (6, 2, 64), 50000),        # one action token per step, d = 64, G = 3
+    ((300, 70, 30, 7), (8, 8, 128), 3),          # long action chunks, G = 1: a tile meets two holes
+])
+def test_isolated_pack_appended_with_its_own_ids(dims, heads, pos0):
+    """evl_isolated_pack_append (keys rotated at the ids the mask implies) followed by
+    evl_isolated_pack_attention, which then is one causal launch with the earlier steps' action
+    tokens as holes: against the oracle's dense-mask definition on all rows, against the route
+    through evl_rope_append (per-run query shifts) to rounding, and again for fewer frames than
+    were appended.  The stored keys carry the pack's ids: checked on the cache contents."""
+    import paper_2512_10310_amd as evl
+    from harness import GpuLayer, check_close, dev_bf16, host_f32, PAGE
+    prefix, F, A, N = dims
+    Hq, Hkv, d = heads
+    shape = StreamShape(Hq, Hkv, d, 1e6, prefix, F, A)
+    q, k, v = pack_inputs(shape, prefix, F, A, N, 83)
+    L = q.shape[0]
+    want = oracle.isolated_pack(q, k, v, prefix, F, A, N, pos0, shape.rope_base)
+    packed = GpuLayer(shape, [L], random_pages=True, out_f32=True, cfg=84)
+    plain = GpuLayer(shape, [L], random_pages=True, out_f32=True, cfg=85)
+    packed.cache.isolated_pack_append(dev_bf16(k), dev_bf16(v), pos0, prefix, F, A, N)
+    plain.append(k, v, pos0)
+    assert packed.cache.len() == L and packed.cache.pos0() == pos0
+    qd = dev_bf16(q)
+    out_a, out_b = packed.new_out(L), plain.new_out(L)
+    before = packed.cache.launches()
+    packed.cache.isolated_pack_attention(qd, prefix, F, A, N, out_a)
+    took = packed.cache.launches() - before
+    plain.cache.isolated_pack_attention(qd, prefix, F, A, N, out_b)
+    torch.cuda.synchronize()
+    got_a, got_b = host_f32(out_a), host_f32(out_b)
+    print("pack %s: %d launches, plan %s" % (dims, took, packed.cache.last_plan()))
+    check_close(got_a, want, MAX_ABS, MEAN_ABS, "pack ids %s" % (dims,))
+    check_close(got_a, got_b, MAX_ABS, MEAN_ABS, "pack ids against the shifted-query route %s" % (dims,))
+    assert took <= 2        # attention (+ merge of the pieces, if the key range was cut)
+    # position tags: instruction and visual tokens numbered without a gap, action tokens behind their frame
+    _, _, tags = packed.pools_host()
+    for t in sorted({0, prefix - 1, prefix, prefix + F - 1, prefix + F, prefix + F + A - 1, prefix + F + A, L - 1}):
+        s = 0 if t < prefix else (t - prefix) // (F + A)
+        assert tags[oracle.slot(packed.table_np[0], PAGE, t)] == pos0 + t - A * s, t
+    # fewer frames of the same pack
+    M = N // 2
+    Lm = prefix + M * (F + A)
+    out_m = packed.new_out(Lm)
+    packed.cache.isolated_pack_attention(qd, prefix, F, A, M, out_m)
+    torch.cuda.synchronize()
+    check_close(host_f32(out_m), want[:Lm], MAX_ABS, MEAN_ABS, "pack ids, %d of %d frames" % (M, N))
+    # a sequence that holds a pack takes nothing else until it is reset
+    with pytest.raises(evl.EvlError) as e:
+        packed.cache.rope_append(dev_bf16(k[:1]), dev_bf16(v[:1]), pos0 + L, 1)
+    assert e.value.status == "EVL_ERR_NONCONTIGUOUS"
+    with pytest.raises(evl.EvlError) as e:
+        packed.cache.chunk_attention(qd, 0, 4, out_a)
+    assert e.value.status == "EVL_ERR_ARG"
+    packed.cache.reset()
+    assert packed.cache.len() == 0
+
+
+def test_isolated_pack_append_refuses_what_it_does_not_serve():
+    import paper_2512_10310_amd as evl
+    from harness import GpuLayer
+    shape = LAYER7B
+    layer = GpuLayer(shape, [4000], out_f32=True)
+    for args in ((10, 196, 8, 2), (256, 40, 8, 2), (256, 196, 0, 2)):     # short instruction, short steps, no action tokens
+        with pytest.raises(evl.EvlError) as e:
+            layer.cache.isolated_pack_append(0x1000, 0x1000, 0, *args)
+        assert e.value.status == "EVL_ERR_UNSUPPORTED", args
+    assert layer.cache.len() == 0 and layer.cache.launches() == 0
