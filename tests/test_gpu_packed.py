@@ -161,6 +161,40 @@ def test_isolated_pack_appended_with_its_own_ids(dims, heads, pos0):
     assert packed.cache.len() == 0
 
 
+def random_pack(seed):
+    """A served pack shape drawn from the seed: instruction of 63..400 tokens, steps of 64..300 tokens
+    (half of them under 100) with 1..48 action tokens among them, 1..10 steps, one of five head shapes, any start position."""
+    rng = np.random.default_rng(8300 + seed)
+    Hq, Hkv, d = [(28, 4, 128), (8, 8, 128), (6, 2, 64), (16, 2, 128), (12, 4, 64)][int(rng.integers(5))]
+    prefix = int(rng.integers(63, 401))
+    step = int(rng.integers(64, 301)) if rng.integers(2) else int(rng.integers(64, 100))   # short steps: two holes in a tile
+    A = int(rng.integers(1, min(48, step - 1) + 1))
+    F = step - A
+    N = int(rng.integers(1, 11))
+    pos0 = int(rng.integers(0, 60000))
+    return (prefix, F, A, N), (Hq, Hkv, d), pos0
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_isolated_pack_with_its_own_ids_random_shapes(seed):
+    """Seeded shapes of the one-launch pack route (holes at every alignment to the 64-key tiles, one or
+    two holes per tile, packs that end inside a tile) against the oracle's dense-mask definition."""
+    from harness import GpuLayer, check_close, dev_bf16, host_f32
+    (prefix, F, A, N), (Hq, Hkv, d), pos0 = random_pack(seed)
+    shape = StreamShape(Hq, Hkv, d, 1e6, prefix, F, A)
+    q, k, v = pack_inputs(shape, prefix, F, A, N, 8300 + seed)
+    L = q.shape[0]
+    print("seed %d: prefix %d, %d steps of %d + %d tokens, heads %s, pos0 %d" % (seed, prefix, N, F, A, (Hq, Hkv, d), pos0),
+          flush=True)
+    want = oracle.isolated_pack(q, k, v, prefix, F, A, N, pos0, shape.rope_base)
+    layer = GpuLayer(shape, [L], random_pages=True, out_f32=True, cfg=8400 + seed)
+    layer.cache.isolated_pack_append(dev_bf16(k), dev_bf16(v), pos0, prefix, F, A, N)
+    out = layer.new_out(L)
+    layer.cache.isolated_pack_attention(dev_bf16(q), prefix, F, A, N, out)
+    torch.cuda.synchronize()
+    check_close(host_f32(out), want, MAX_ABS, MEAN_ABS, "random pack, seed %d" % seed)
+
+
 def test_isolated_pack_append_refuses_what_it_does_not_serve():
     import paper_2512_10310_amd as evl
     from harness import GpuLayer
