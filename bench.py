@@ -347,17 +347,21 @@ def main():
     if not args.no_extra:
         from synth import ragged_cache_lengths
 
-        def timed_ms(fn, reps, warm=3):
-            for _ in range(warm):
+        def timed_ms(fn, reps, warm=3, calls=1):
+            """p50 over `reps` event pairs of the time of one fn(); short steps are timed `calls` at a time,
+            back to back as a serving loop issues them (an event pair around a single 15 us step measures the
+            pair and an idling chip as much as the step)."""
+            for _ in range(warm * calls):
                 fn()
             torch.cuda.synchronize()
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
             for a, b in evs:
                 a.record(stream)
-                fn()
+                for _ in range(calls):
+                    fn()
                 b.record(stream)
             torch.cuda.synchronize()
-            return float(np.median([a.elapsed_time(b) for a, b in evs]))
+            return float(np.median([a.elapsed_time(b) for a, b in evs])) / calls
 
         # 16 episodes, cached lengths uniform in [2048, 65536], one 204-token chunk each, one launch
         lens = ragged_cache_lengths(16, 2048, 65536).tolist()
@@ -425,8 +429,8 @@ def main():
             cW.rope_append(kW[W - n:], vW[W - n:], W - n, n)
             cW.chunk_attention(qW[W - n:], W - n, n, outW[:n])
 
-        msA = timed_ms(reprefill_step, 50)
-        msB = timed_ms(reuse_step, 50)
+        msA = timed_ms(reprefill_step, 50, calls=5)
+        msB = timed_ms(reuse_step, 50, calls=10)
         result["redundancy"] = {
             "workload": "configs[4]: (A) full causal re-prefill of the 16-frame window (%d tokens) each step vs "
                         "(B) cache reuse: %d cached + %d new" % (W, W - n, n),
@@ -459,8 +463,8 @@ def main():
                 cS.rope_append(k_new, v_new, Cs, n)
                 cS.chunk_attention(q_new, Cs, n, out)
 
-            ms_s = timed_ms(sampled_step, 50)
-            ms_w = timed_ms(whole_step, 50)
+            ms_s = timed_ms(sampled_step, 50, calls=10)
+            ms_w = timed_ms(whole_step, 50, calls=10)
             series.append({"frames_seen": seen, "cached_tokens": Cs, "retained_tokens": kept,
                            "sampled_ms": round(ms_s, 4), "whole_history_ms": round(ms_w, 4),
                            "sampled_attention_TFLOPs": round(attention_flops(Hq, d, kept, n) / (ms_s * 1e-3) / 1e12, 1)})
@@ -480,7 +484,7 @@ def main():
                     cS.truncate(Cs)
                     cS.rope_append(k_new[:nd], v_new[:nd], Cs, nd)
                     cS.chunk_attention(q_new[:nd], Cs, nd, out[:nd])
-                ms_d = timed_ms(decode_step, 50)
+                ms_d = timed_ms(decode_step, 50, calls=10)
                 kv_bytes = 2 * (Cs + nd) * Hkv * d * 2
                 dec.append({"cached_tokens": Cs, "history": label, "n_new": nd, "ms": round(ms_d, 4),
                             "kv_read_GBps": round(kv_bytes / (ms_d * 1e-3) / 1e9, 1),
@@ -504,7 +508,7 @@ def main():
             cS.truncate(Cd)
             cS.rope_append(k_new[:1], v_new[:1], Cd, 1)
             cS.chunk_attention_sampled(q_new[:1], runs_d, Cd, 1, out[:1])
-        ms_sd = timed_ms(sampled_decode_step, 50)
+        ms_sd = timed_ms(sampled_decode_step, 50, calls=10)
         dec.append({"cached_tokens": Cd, "history": "prefix + 17 of 100 frames retained (%d tokens)" % kept_d,
                     "n_new": 1, "ms": round(ms_sd, 4),
                     "kv_read_GBps": round(2 * (kept_d + 1) * Hkv * d * 2 / (ms_sd * 1e-3) / 1e9, 1),
@@ -512,7 +516,7 @@ def main():
         def fused_sampled_decode_step():
             cS.truncate(Cd)
             cS.step_sampled(q_new[:1], k_new[:1], v_new[:1], runs_d, Cd, 1, out[:1])
-        ms_fsd = timed_ms(fused_sampled_decode_step, 50)
+        ms_fsd = timed_ms(fused_sampled_decode_step, 50, calls=10)
         dec.append({"cached_tokens": Cd, "history": "prefix + 17 of 100 frames retained (%d tokens), evl_step_sampled "
                                                     "(one launch)" % kept_d,
                     "n_new": 1, "ms": round(ms_fsd, 4),
@@ -524,18 +528,19 @@ def main():
             def fused_decode_step():
                 cS.truncate(Cs)
                 cS.step(q_new[:1], k_new[:1], v_new[:1], Cs, 1, out[:1])
-            ms_f = timed_ms(fused_decode_step, 50)
+            ms_f = timed_ms(fused_decode_step, 50, calls=10)
             kv_bytes = 2 * (Cs + 1) * Hkv * d * 2
             dec.append({"cached_tokens": Cs, "history": label + ", evl_step (one launch)", "n_new": 1,
                         "ms": round(ms_f, 4), "kv_read_GBps": round(kv_bytes / (ms_f * 1e-3) / 1e9, 1),
                         "frac_of_hbm_peak": round(kv_bytes / (ms_f * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)})
         result["decode_shape"] = {
             "workload": "one layer, step = rope_append + chunk_attention[_sampled] of 1 or 4 new tokens; bytes = K "
-                        "and V of the attended tokens once",
+                        "and V of the attended tokens once; p50 over 50 groups of 10 steps issued back to back",
             "steps": dec}
         result["sampled_history"] = {
             "workload": "one layer; prefix 256 + 16 uniformly sampled frames of 204 tokens retained out of "
-                        "the frames seen so far, 204 new tokens; step = rope_append + chunk_attention_sampled",
+                        "the frames seen so far, 204 new tokens; step = rope_append + chunk_attention_sampled; p50 over 50 "
+                        "groups of 10 steps issued back to back",
             "steps": series[::-1]}
         del layersS, keepS, cS
 
