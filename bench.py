@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0
 # when the source has changed since.  Beside it the line carries the bytes the launch must move
 # by construction ("traffic_modelled": K and V once, the queries once per piece of the key
 # range, the partial rows of every piece), which cannot go stale.
-ATTN_TRAFFIC_BYTES_PER_LAUNCH = 41.37e6
-ATTN_TRAFFIC_MEASURED_ON_SHA1 = "808138f6de37fef092f5ee1675e58e992d617729"
+ATTN_TRAFFIC_BYTES_PER_LAUNCH = 41.36e6
+ATTN_TRAFFIC_MEASURED_ON_SHA1 = "49f1fbf344d941bbd45c088fbfa60ae5499d78cd"
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_10310_amd", "csrc",
                              "evl_kernels.hip")
 

@@ -363,14 +363,70 @@ static void init_params(const evl_cache *c, const void *q_new, void *out, void *
     cp->out_f32 = p->out_f32;
 }
 
-// Work-groups entry i of a launch puts on each XCD: its (KV head, split) groups, cut into chunks
-// of at most kXcdChunkRowTiles row tiles, go round-robin over the 8 XCDs, starting at XCD i % 8;
-// the kernel recomputes the same assignment from (XCD, slot).
-static void add_xcd_load(int per_xcd[8], int i, int groups, int m_tiles) {
-    const int chunks = groups * evl::xcd_chunks_per_group(m_tiles), rows = evl::xcd_chunk_rows(m_tiles);
+// How an entry's work items (groups x m_tiles) are cut into XCD chunks (see evl_internal.h), and
+// what the cut puts on the fullest shader engine of the chip.
+struct Chunking {
+    int rows, pad;   // AttnSeq::chunk_rows, chunk_pad
+    int engine;      // real work-groups on the fullest shader engine (of an entry dealt from XCD 0)
+};
+
+// Real work-groups on the fullest shader engine for one way of cutting.  The chunks go to the
+// XCDs in turn; an XCD deals its slots (padding included) to its four engines in turn.
+static int engine_load(int groups, int m_tiles, int rows, int pad) {
+    const int chunks = evl::xcd_chunks(groups, m_tiles, rows, pad);
+    int worst = 0;
+    if (!pad) {  // all slots real except the tail of the entry's last chunk
+        for (int x = 0; x < 8 && x < chunks; ++x) {
+            int w = (chunks - x + 7) / 8 * rows;
+            if ((chunks - 1) % 8 == x) w -= chunks * rows - groups * m_tiles;
+            worst = std::max(worst, (w + evl::kEnginesPerXcd - 1) / evl::kEnginesPerXcd);
+        }
+        return worst;
+    }
+    // padded: a chunk's slots are a multiple of 4 (asserted by the caller's choice of 8), so slot i of any
+    // chunk goes to engine i % 4: a full chunk puts rows / 4 on each, a group's last chunk of
+    // `last` real items (last + 3) / 4 on the fullest.  Group g's last chunk is chunk g * cpg + cpg - 1.
+    const int cpg = (m_tiles + rows - 1) / rows, last = m_tiles - (cpg - 1) * rows;
+    int lasts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int g = 0; g < groups; ++g) ++lasts[(g * cpg + cpg - 1) % 8];
+    for (int x = 0; x < 8 && x < chunks; ++x) {
+        const int here = (chunks - x + 7) / 8;
+        worst = std::max(worst, (here - lasts[x]) * (rows / evl::kEnginesPerXcd) +
+                                    lasts[x] * ((last + evl::kEnginesPerXcd - 1) / evl::kEnginesPerXcd));
+    }
+    return worst;
+}
+
+// The cut for an entry: groups of at most kXcdChunkRowTiles row tiles are chunks by themselves.
+// Otherwise the candidates are chunks of 8 cut group by group with padding, chunks of a divisor
+// of m_tiles between 4 and 7 (dense, no padding, no straddling), and chunks of 8 cut densely
+// (straddling groups); the one that needs the fewest rounds of work-groups on the fullest shader
+// engine wins, ties going to them in that order, larger divisors first -- the order measured for
+// launches of many rounds (a 4000-token prefill: 138 us padded, 147 us dense by 8, 153 us by 5).
+static Chunking choose_chunking(int groups, int m_tiles) {
+    const int cus = evl::kCusPerXcd / evl::kEnginesPerXcd;
+    if (m_tiles <= evl::kXcdChunkRowTiles) {
+        const int rows = std::max(m_tiles, 1);
+        return Chunking{rows, 0, engine_load(groups, m_tiles, rows, 0)};
+    }
+    Chunking best{evl::kXcdChunkRowTiles, 1, engine_load(groups, m_tiles, evl::kXcdChunkRowTiles, 1)};
+    auto consider = [&](int rows, int pad) {
+        const int e = engine_load(groups, m_tiles, rows, pad);
+        if ((e + cus - 1) / cus < (best.engine + cus - 1) / cus) best = Chunking{rows, pad, e};
+    };
+    for (int rows = evl::kXcdChunkRowTiles - 1; rows >= evl::kXcdChunkRowTiles / 2; --rows)
+        if (m_tiles % rows == 0) consider(rows, 0);
+    consider(evl::kXcdChunkRowTiles, 0);
+    return best;
+}
+
+// Work-groups entry i of a launch puts on each XCD: its chunks go round-robin over the 8 XCDs,
+// starting at XCD i % 8; the kernel recomputes the same assignment from (XCD, slot).
+static void add_xcd_load(int per_xcd[8], int i, int groups, int m_tiles, const Chunking &ck) {
+    const int chunks = evl::xcd_chunks(groups, m_tiles, ck.rows, ck.pad);
     for (int x = 0; x < 8; ++x) {
         const int r = (x - i) & 7;
-        per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * rows;
+        per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * ck.rows;
     }
 }
 
@@ -393,42 +449,70 @@ static bool unsplit_wins(double work_tiles, double longest, double items, double
     return whole <= split;
 }
 
-// Number of pieces for a launch that serves ONE set of rows (one sequence's chunk), by the same
-// kind of pricing, fitted to measurements over a grid of history and chunk lengths.  It knows
-// that work-groups come in rounds of one per CU (336 equal work-groups take two rounds and leave
-// the second two-thirds empty, 224 take one), that a key tile is cheaper the more row tiles
-// share the keys in their XCD's L2 (1.65 us with the 6 row tiles of a 204-token chunk, under
-// 1.3 us with 50 or more), and that launches of more work-groups than CUs have run a quarter
-// above this arithmetic, split ones a half (with every CU busy the clock is lower, and rounds
-// do not pack as tightly as counted).
-// base_items: work items without a split; m_tiles: row tiles; tiles: key tiles of the longest
-// work item; work_tiles: key tiles over all of them; uniformity: shortest over longest work item
-// without the split (1 for a chunk over a long history, near 0 for a prefill, whose items the
-// in-order dispatch packs well whatever their number); rows * row_bytes: one copy of the partial
-// rows; capacity: room for them.  Returns the number of pieces (1 = no split), their length in
-// *tps_out.
-static int pick_pieces(int base_items, int m_tiles, int64_t tiles, double work_tiles, double uniformity,
-                       size_t rows, size_t row_bytes, size_t capacity, int *tps_out) {
-    const double kFixed = 7.0, kBytesPerUs = 4.0e6, kMerge = 5.0, kCus = 256.0;
-    const double kManyRounds = 1.25, kManyRoundsSplit = 1.5;
-    const double tile_us = 1.25 + 0.4 * std::min(1.0, 6.0 / std::max(m_tiles, 1));
+// Number of pieces for a launch that serves ONE set of rows (one sequence's chunk): every
+// candidate is priced with a model of how the chip runs the launch, fitted to timings of forced
+// plans over a grid of history and chunk lengths (8 histories from 0 to 60 000 tokens, 15 chunk
+// lengths from 40 to 4000, up to 13 piece counts each; 7B-class heads).  What the model knows:
+//  * Work-groups run one per compute unit, and the hardware deals them to the 8 XCDs in turn and,
+//    inside an XCD, to its 4 shader engines of 8 compute units in turn: the fullest shader
+//    engine's work-groups, in rounds of 8, set the pace (252 equal work-groups that put 33 on
+//    one XCD take two rounds, 240 that put 30 on each take one).  The load of the fullest XCD
+//    follows from the work-item map (xcd_chunks, xcd_chunk_rows).
+//  * Equal pieces come in whole rounds; the unequal items of a causal chunk over a short history
+//    pack better than that, the more so the less uniform they are, but leave a tail.
+//  * A key tile costs a work-group 1.2 to 1.5 us: less when few row tiles share the keys, more
+//    when every compute unit is busy (the clock is lower then).
+//  * A split costs the merge launch and the partial rows, written once and read once.
+// see[mt]: key tiles row tile mt sees under the causal mask, non-decreasing; tiles: key tiles of
+// the whole range (the longest work item without a split); rows * row_bytes: one copy of the
+// partial rows; capacity: room for them.  A split has to beat the unsplit launch by 5 % of the
+// model's time to be taken (where the two are close the model errs towards splitting, and the
+// unsplit launch needs no workspace).  Returns the number of pieces (1 = no split), their length
+// in key tiles in *tps_out.
+static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tiles, size_t rows, size_t row_bytes,
+                       size_t capacity, int *tps_out) {
+    const double kTile = 1.346, kTileFewRows = -0.169, kTileBusy = 0.187, kFixed = 5.825, kMerge = 10.0,
+                 kPerMB = 0.264, kTail = 0.325, kUnsplitMargin = 1.05;
+    const int m_tiles = (int)see.size();
+    double work = 0.0;
+    for (int v : see) work += v;
+    const int see_min = see.front(), see_max = see.back();
     int best_n = 1, best_tps = (int)tiles;
-    double best_t = 0.0;
-    for (int64_t want = 1; want <= std::min<int64_t>(kMaxSplits, tiles); ++want) {
+    double best_t = 0.0, unsplit_t = 0.0;
+    const int64_t most = std::min<int64_t>(kMaxSplits, tiles);
+    for (int64_t want = 1; want <= most; want += want < 32 ? 1 : want / 8) {
         const int64_t tps = (tiles + want - 1) / want, n = (tiles + tps - 1) / tps;
-        if (n != want) continue;  // the same plan as a smaller `want`
+        if (n != want && want <= 32) continue;  // the same plan as a smaller `want`
         if (n > 1 && (tps < kMinTilesPerSplit || (size_t)n * rows * row_bytes > capacity)) continue;
-        const double items = (double)base_items * (double)n;
-        const double rounds = std::ceil(items / kCus) / (items / kCus);
-        const double packing = n > 1 ? rounds : 1.0 + (rounds - 1.0) * uniformity;  // pieces are equal
-        double t = std::max((double)tps * tile_us + kFixed, packing * (work_tiles * tile_us + items * kFixed) / kCus);
-        if (items > kCus) t *= n > 1 ? kManyRoundsSplit : kManyRounds;
-        if (n > 1) t += 2.0 * (double)((size_t)n * rows * row_bytes) / kBytesPerUs + kMerge;
+        // work items that see any key: piece s of row tile mt does if see[mt] > s * tps
+        int64_t live = 0;
+        for (int64_t sp = 0; sp < n; ++sp) {
+            if (sp * tps < see_min)
+                live += m_tiles;
+            else
+                live += see.end() - std::upper_bound(see.begin(), see.end(), (int)(sp * tps));
+        }
+        const double longest = (double)std::min<int64_t>(tps, see_max);
+        const double mean = work / ((double)m_tiles * (double)n);
+        const double uniform = n == 1 ? (double)see_min / (double)see_max : mean / longest;
+        const double busy = std::min(1.0, (double)(live * n_kv_heads) / 256.0);
+        // work-groups on the fullest shader engine, in rounds of its 8 compute units
+        const double engine = (double)choose_chunking((int)n * n_kv_heads, m_tiles).engine / 8.0;
+        const double rounds = engine + (std::ceil(engine) - engine) * uniform;
+        const double tile_us = kTile + kTileFewRows * std::min(1.0, 6.0 / m_tiles) + kTileBusy * busy;
+        double t = std::max(longest * tile_us + kFixed,
+                            rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
+        if (n > 1) t += kMerge + kPerMB * (double)((size_t)n * rows * row_bytes) * 1e-6;
+        if (n == 1) unsplit_t = t;
         if (want == 1 || t < best_t) {
             best_t = t;
             best_n = (int)n;
             best_tps = (int)tps;
         }
+    }
+    if (best_n > 1 && unsplit_t > 0.0 && unsplit_t <= kUnsplitMargin * best_t) {
+        best_n = 1;
+        best_tps = (int)tiles;
     }
     *tps_out = best_tps;
     return best_n;
@@ -784,8 +868,11 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
             items_split += (double)m_tiles[i] * Hkv * n_splits[i];
         }
         if (n_seqs == 1) {  // one set of rows: the number of pieces is searched, not derived from a target
-            n_splits[0] = pick_pieces((int)base_items, m_tiles[0], tiles[0], work, shortest / longest, (size_t)n_new[0] * Hq,
-                                      row_bytes, c->d.workspace ? partials_capacity(c) : 0, &tps[0]);
+            std::vector<int> see(m_tiles[0]);  // key tiles row tile mt sees under the causal mask
+            for (int mt = 0; mt < m_tiles[0]; ++mt)
+                see[mt] = (cache_lens[0] + (std::min((mt + 1) * MT, n_new[0] * G) - 1) / G + 1 + KN - 1) / KN;
+            n_splits[0] = pick_pieces(see, Hkv, tiles[0], (size_t)n_new[0] * Hq, row_bytes,
+                                      c->d.workspace ? partials_capacity(c) : 0, &tps[0]);
             ws_rows = n_splits[0] > 1 ? (size_t)n_splits[0] * n_new[0] * Hq : 0;
         } else if (unsplit_wins(work, longest, (double)base_items, longest_split, items_split, ws_rows * row_bytes)) {
             for (int i = 0; i < n_seqs; ++i) {
@@ -850,7 +937,10 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
             q.part_off = (int64_t)part_off;
             q.q_pos = (int32_t)(c->pos0[seq_ids[k]] + cache_lens[k]);
             const int groups = n_splits[k] * Hkv;
-            add_xcd_load(per_xcd, i, groups, m_tiles[k]);
+            const Chunking ck = choose_chunking(groups, m_tiles[k]);
+            q.chunk_rows = ck.rows;
+            q.chunk_pad = ck.pad;
+            add_xcd_load(per_xcd, i, groups, m_tiles[k], ck);
             items += m_tiles[k] * groups;
             plan.max_splits = std::max(plan.max_splits, n_splits[k]);
             if (n_splits[k] > 1) {
@@ -1130,6 +1220,22 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
         T *= 2;
     }
 
+    // one group and no target set by the caller: the number of pieces is priced like the plain call's
+    // (a history handed over as one run then gets the plain call's plan, and its bits)
+    if (n_groups == 1 && !c->tuned) {
+        std::vector<int> see(m_tiles);  // key tiles row tile mt sees: all of the runs, the chunk up to its own tokens
+        const Entry &last = ent.back();
+        for (int mt = 0; mt < m_tiles; ++mt) {
+            const int last_tok = (std::min((mt + 1) * MT, n_new * G) - 1) / G;
+            const int64_t stop = std::min<int64_t>(last.stop, (int64_t)cache_len + last_tok + 1);
+            see[mt] = (int)(all_tiles - last.tiles + entry_tiles(last.begin, (int32_t)std::max<int64_t>(stop, last.begin + 1)));
+        }
+        g_splits[0] = pick_pieces(see, Hkv, all_tiles, (size_t)n_new * Hq, row_bytes,
+                                  c->d.workspace ? partials_capacity(c) : 0, &g_tps[0]);
+        total_splits = g_splits[0];
+        ws_rows = total_splits > 1 ? (size_t)total_splits * n_new * Hq : 0;
+    }
+
     void *part_o = c->d.workspace;
     float *part_ml = part_o ? (float *)((char *)part_o + ws_rows * D * esz) : nullptr;
     Plan plan;
@@ -1163,8 +1269,11 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
             q.total_splits = total_splits;
             q.part_off = 0;
         }
+        const Chunking ck = choose_chunking(g_splits[g] * Hkv, m_tiles);
+        p.seq[0].chunk_rows = ck.rows;
+        p.seq[0].chunk_pad = ck.pad;
         int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        add_xcd_load(per_xcd, 0, g_splits[g] * Hkv, m_tiles);
+        add_xcd_load(per_xcd, 0, g_splits[g] * Hkv, m_tiles, ck);
         p.n_items = m_tiles * g_splits[g] * Hkv;
         p.items_per_xcd = *std::max_element(per_xcd, per_xcd + 8);
         plan.n_items += p.n_items;
@@ -1401,7 +1510,10 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
                 q.total_splits = gr.n_splits;
                 q.part_off = (int64_t)part_off;
             }
-            add_xcd_load(per_xcd, at, gr.n_splits * Hkv, gr.m_tiles);
+            const Chunking ck = choose_chunking(gr.n_splits * Hkv, gr.m_tiles);
+            p.seq[at].chunk_rows = ck.rows;
+            p.seq[at].chunk_pad = ck.pad;
+            add_xcd_load(per_xcd, at, gr.n_splits * Hkv, gr.m_tiles, ck);
             items += gr.m_tiles * gr.n_splits * Hkv;
             plan.max_splits = std::max(plan.max_splits, gr.n_splits);
             if (gr.n_splits > 1) {

@@ -66,6 +66,8 @@ struct AttnSeq {
     int32_t total_splits;     // pieces over all groups of the rows (1 = write `out` directly)
     int32_t cnt_base;         // decode kernel: first ticket counter of the rows (one per KV head)
     int32_t k_pos;            // fused step: position id of the chunk's first token (the key side)
+    int32_t chunk_rows;       // attention kernel: work items per XCD chunk (first entry of a group), ...
+    int32_t chunk_pad;        // ... and 1 if every (KV head, piece) group is cut and padded by itself
     int64_t part_off;         // first partial row of the rows' block in the workspace
 };
 
@@ -116,16 +118,24 @@ constexpr size_t attention_stage_bytes(int head_dim) {  // one K tile + one V ti
     return (size_t)2 * kKeyTile * head_dim * 2;
 }
 inline int attention_rows_per_workgroup() { return kAttnRows; }
-// The row tiles of one (sequence, KV head, split) group are dealt to the XCDs in chunks of at most
-// this many (a chunk stays on one XCD and shares its L2); the last chunk of a group is padded with
-// work items that exit at once.  Host (grid size) and kernel (work-item map) both count with these.
+// Work items of an entry -- its (KV head, piece) groups of m_tiles row tiles each -- are dealt to
+// the XCDs in chunks of chunk_rows items that take consecutive slots of one XCD, where they share
+// keys in the L2.  Two ways of cutting, chosen by the host per entry (AttnSeq::chunk_rows,
+// chunk_pad) and obeyed by the kernel's work-item map:
+//  * padded (chunk_pad = 1): every group is cut by itself; a group's last chunk is padded to
+//    chunk_rows slots with work items that exit at once.  No chunk straddles two groups.
+//  * dense (chunk_pad = 0): the items of all groups, laid end to end, are cut; only the entry's
+//    last chunk can be short.  A chunk straddles groups unless chunk_rows divides m_tiles.
+// The hardware deals an XCD's work-groups to its four shader engines in turn, so padding in the
+// middle of an XCD's list leaves the engines with unequal numbers of real work-groups: with equal
+// items in one or two rounds that costs a whole round, which is what the dense cut is for.
 constexpr int kXcdChunkRowTiles = 8;
-__host__ __device__ inline int xcd_chunk_rows(int m_tiles) {
-    return m_tiles < 1 ? 1 : (m_tiles < kXcdChunkRowTiles ? m_tiles : kXcdChunkRowTiles);
-}
-__host__ __device__ inline int xcd_chunks_per_group(int m_tiles) {
-    const int rows = xcd_chunk_rows(m_tiles);
-    return m_tiles < 1 ? 1 : (m_tiles + rows - 1) / rows;
+constexpr int kCusPerXcd = 32, kEnginesPerXcd = 4;
+// chunks of an entry with `groups` groups
+__host__ __device__ inline int xcd_chunks(int groups, int m_tiles, int chunk_rows, int chunk_pad) {
+    if (m_tiles < 1 || chunk_rows < 1) return 0;
+    return chunk_pad ? groups * ((m_tiles + chunk_rows - 1) / chunk_rows)
+                     : (groups * m_tiles + chunk_rows - 1) / chunk_rows;
 }
 // Dynamic LDS bytes the attention kernel needs: the tile ring, then a region that first holds
 // the cos/sin table of the prologue (tab_tokens tokens) and, in launches whose work-groups walk

@@ -601,12 +601,13 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
 
     // XCD-aware work-group -> work-item map.  The hardware deals work-groups round-robin to
     // the 8 XCDs, each with its own L2: work-group b runs on XCD b % 8 and is that XCD's
-    // slot b / 8.  The row tiles of one (sequence, KV head, split) group read the same K/V, so
-    // a group's items take consecutive slots of one XCD -- in chunks of at most
-    // kXcdChunkRowTiles row tiles, so that a chunk of many row tiles (a long prefill) does not
-    // pin a whole group to one XCD; the chunks of sequence i go round-robin over the XCDs
-    // starting at XCD i % 8, which spreads every sequence -- long or short -- over the whole
-    // chip.  Sequences are listed longest first.
+    // slot b / 8.  An entry's work items -- its (KV head, split) groups of m_tiles row tiles --
+    // are cut into chunks of chunk_rows items (group by group, or all groups end to end: the
+    // host's choice per entry); the row tiles of one group read the same K/V, so a chunk takes
+    // consecutive slots of one XCD -- chunks of at most kXcdChunkRowTiles items, so that a group
+    // of many row tiles (a long prefill) is not pinned to one XCD; the chunks of entry i go
+    // round-robin over the XCDs starting at XCD i % 8, which spreads every sequence -- long or
+    // short -- over the whole chip.  Sequences are listed longest first.
     const int G = p.group, Hq = p.n_q_heads, Hkv = p.n_kv_heads;
     const int xcd = blockIdx.x % 8;
     int local = blockIdx.x / 8;
@@ -614,8 +615,8 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     if (p.n_seqs <= 4) {  // a few entries: a scalar walk is the shortest
         for (int e = 0; e < p.n_seqs; ++e) {
             const int r = (xcd - e) & 7;  // first chunk of entry e that lands on this XCD
-            const int mtl = xcd_chunk_rows(p.seq[e].m_tiles);
-            const int chunks = p.seq[e].n_splits * Hkv * xcd_chunks_per_group(p.seq[e].m_tiles);
+            const int mtl = max(p.seq[e].chunk_rows, 1);
+            const int chunks = xcd_chunks(p.seq[e].n_splits * Hkv, p.seq[e].m_tiles, p.seq[e].chunk_rows, p.seq[e].chunk_pad);
             const int here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
             if (local < here) {
                 s = e;
@@ -633,8 +634,8 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
         const int ln = threadIdx.x & 63, e = e0 + ln;
         int here = 0, r = 0, mtl = 1;
         if (e < p.n_seqs) {
-            const int chunks = p.seq[e].n_splits * Hkv * xcd_chunks_per_group(p.seq[e].m_tiles);
-            mtl = xcd_chunk_rows(p.seq[e].m_tiles);
+            const int chunks = xcd_chunks(p.seq[e].n_splits * Hkv, p.seq[e].m_tiles, p.seq[e].chunk_rows, p.seq[e].chunk_pad);
+            mtl = max(p.seq[e].chunk_rows, 1);
             r = (xcd - e) & 7;  // first chunk of entry e that lands on this XCD
             here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
         }
@@ -659,15 +660,27 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     gs = __builtin_amdgcn_readfirstlane(gs);
     local = __builtin_amdgcn_readfirstlane(local);
     const AttnSeq sq = p.seq[s];
-    // gs counts the entry's chunks: chunk gs % cpg of (KV head, split) group gs / cpg
-    const int cpg = xcd_chunks_per_group(sq.m_tiles), mtl = xcd_chunk_rows(sq.m_tiles);
-    const int mt_up = (gs % cpg) * mtl + local % mtl;
-    if (mt_up >= sq.m_tiles) return;  // padding of a group's last chunk
+    // gs counts the entry's chunks.  Padded cut: chunk gs % cpg of group gs / cpg.  Dense cut: the
+    // chunk holds items gs * mtl .. of the entry, item u being row tile u % m_tiles (counted from
+    // the last) of group u / m_tiles.
+    const int mtl = max(sq.chunk_rows, 1);
+    int grp, mt_up;
+    if (sq.chunk_pad) {
+        const int cpg = (sq.m_tiles + mtl - 1) / mtl;
+        grp = gs / cpg;
+        mt_up = (gs - grp * cpg) * mtl + local % mtl;
+        if (mt_up >= sq.m_tiles) return;  // padding of a group's last chunk
+    } else {
+        const int u = gs * mtl + local % mtl;
+        if (u >= sq.n_splits * Hkv * sq.m_tiles) return;  // padding of the entry's last chunk
+        grp = u / sq.m_tiles;
+        mt_up = u - grp * sq.m_tiles;
+    }
     // last row tile first: under the causal mask it sees the most keys, and the longest
     // work-groups should not be the ones that start last
     const int mt = sq.m_tiles - 1 - mt_up;
-    const int split = (gs / cpg) % sq.n_splits;
-    const int kvh = (gs / cpg) / sq.n_splits;
+    const int split = grp % sq.n_splits;
+    const int kvh = grp / sq.n_splits;
 
     const int R = sq.n_new * G;  // packed rows of this sequence
     const int C = sq.cache_len;

@@ -240,7 +240,7 @@ def plans(path):
     binding._lib = probe
     probe.evl_probe_reset(1)
     for cached, new in ((6580, 204), (20452, 204), (65536, 204), (0, 3520), (0, 256), (5000, 1000), (60000, 500),
-                        (20000, 4000), (3316, 204), (6580, 40)):
+                        (20000, 4000), (3316, 204), (6580, 40), (60000, 100)):
         pages = (cached + new + 15) // 16
         c = binding.Cache(28, 4, 128, 1e6, KPOOL, VPOOL, TABLE, n_pages=pages, max_pages_per_seq=pages,
                           workspace=WS, workspace_bytes=1 << 30)

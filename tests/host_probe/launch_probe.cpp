@@ -203,11 +203,16 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
                     "%s: entry %d disagrees with an earlier group of the same rows", who, e);
             pd.pieces.push_back({sq.split_base, sq.split_base + sq.n_splits});
         }
-        // work items per XCD, as the kernel recomputes them from (XCD, slot)
-        // (a group's row tiles go to the XCDs in chunks of at most kXcdChunkRowTiles, the last one padded)
+        // work items per XCD, as the kernel recomputes them from (XCD, slot): the entry's chunking is the
+        // host's choice among padded chunks (cut group by group) and dense ones (all groups end to end)
         const int groups = sq.n_splits * Hkv;
-        const int chunk_rows = sq.m_tiles < kXcdChunkRowTiles ? sq.m_tiles : kXcdChunkRowTiles;
-        const int chunks = groups * ((sq.m_tiles + chunk_rows - 1) / chunk_rows);
+        const int chunk_rows = sq.chunk_rows;
+        REQUIRE(chunk_rows >= 1 && chunk_rows <= kXcdChunkRowTiles && (sq.chunk_pad == 0 || sq.chunk_pad == 1),
+                "%s: entry %d: chunks of %d work items, pad flag %d", who, e, chunk_rows, sq.chunk_pad);
+        REQUIRE(!sq.chunk_pad || chunk_rows % kEnginesPerXcd == 0,
+                "%s: entry %d: padded chunks of %d slots do not keep the shader engines in step", who, e, chunk_rows);
+        const int chunks = sq.chunk_pad ? groups * ((sq.m_tiles + chunk_rows - 1) / chunk_rows)
+                                        : (groups * sq.m_tiles + chunk_rows - 1) / chunk_rows;
         for (int x = 0; x < 8; ++x) {
             const int r = (x - e) & 7;
             per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * chunk_rows;
@@ -216,6 +221,49 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
         e += sq.n_ent;
     }
     REQUIRE(p.n_items == items, "%s: n_items %d, entries describe %d", who, p.n_items, items);
+    {   // the kernel's work-group -> work-item map, replayed: every (entry, group, row tile) exactly once
+        std::vector<std::vector<char>> seen(p.n_seqs);
+        for (int e = 0; e < p.n_seqs; ++e)
+            if (p.seq[e].n_ent > 0) seen[e].assign((size_t)p.seq[e].n_splits * Hkv * p.seq[e].m_tiles, 0);
+        int64_t mapped = 0;
+        for (int b = 0; b < p.items_per_xcd * 8; ++b) {
+            const int xcd = b % 8;
+            int local = b / 8, s = -1, gs = 0;
+            for (int e = 0; e < p.n_seqs; ++e) {
+                const AttnSeq &en = p.seq[e];
+                const int r = (xcd - e) & 7, mtl = en.chunk_rows > 1 ? en.chunk_rows : 1;
+                const int chunks = xcd_chunks(en.n_splits * Hkv, en.m_tiles, en.chunk_rows, en.chunk_pad);
+                const int here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
+                if (local < here) {
+                    s = e;
+                    gs = r + 8 * (local / mtl);
+                    break;
+                }
+                local -= here;
+            }
+            if (s < 0) continue;
+            const AttnSeq &sq = p.seq[s];
+            const int mtl = sq.chunk_rows > 1 ? sq.chunk_rows : 1;
+            int grp, mt_up;
+            if (sq.chunk_pad) {
+                const int cpg = (sq.m_tiles + mtl - 1) / mtl;
+                grp = gs / cpg;
+                mt_up = (gs - grp * cpg) * mtl + local % mtl;
+                if (mt_up >= sq.m_tiles) continue;
+            } else {
+                const int u = gs * mtl + local % mtl;
+                if (u >= sq.n_splits * Hkv * sq.m_tiles) continue;
+                grp = u / sq.m_tiles;
+                mt_up = u - grp * sq.m_tiles;
+            }
+            REQUIRE(grp >= 0 && grp < sq.n_splits * Hkv, "%s: work-group %d lands in group %d of entry %d", who, b, grp, s);
+            char &mark = seen[s][(size_t)grp * sq.m_tiles + mt_up];
+            REQUIRE(!mark, "%s: work-groups meet at entry %d, group %d, row tile %d", who, s, grp, mt_up);
+            mark = 1;
+            ++mapped;
+        }
+        REQUIRE(mapped == items, "%s: the work-item map reaches %lld of %d work items", who, (long long)mapped, items);
+    }
     REQUIRE(p.items_per_xcd == *std::max_element(per_xcd, per_xcd + 8), "%s: items_per_xcd %d, fullest XCD has %d",
             who, p.items_per_xcd, *std::max_element(per_xcd, per_xcd + 8));
     if (p.hole_width != 0) {  // a pack: one causal key range, at most two holes per key tile, rows of a few keys inside the instruction

@@ -38,7 +38,8 @@ def test_planner_choices_for_known_shapes(probe_lib):
     """What the planner does with a single sequence at the 7B-class layer shape, pinned where
     measurements fixed the right answer: the 204-token step is cut into 10 pieces of one work-group
     per CU (240) at every history length; a prefill is left unsplit (every piece would be a full
-    copy of its rows); mid-size chunks get the piece count that fills one round of work-groups."""
+    copy of its rows); mid-size chunks get the piece count that fills whole rounds of work-groups
+    on every XCD."""
     r = subprocess.run([sys.executable, DRIVER, probe_lib, "plans"], stdout=subprocess.PIPE,
                        stderr=subprocess.STDOUT, text=True, timeout=120)
     assert r.returncode == 0, r.stdout
@@ -47,9 +48,14 @@ def test_planner_choices_for_known_shapes(probe_lib):
     assert got[(6580, 204)] == got[(20452, 204)] == got[(65536, 204)] == got[(3316, 204)] == (240, 10)
     # (the first 63 tokens of a sequence see fewer than 64 keys and go to the few-keys kernel:
     # 3457 and 193 tokens are left for the matrix kernel)
-    assert got[(0, 3520)] == (380, 1) and got[(0, 256)] == (24, 1) and got[(20000, 4000)] == (440, 1)
-    assert got[(5000, 1000)] == (224, 2) and got[(60000, 500)] == (224, 4)
+    assert got[(0, 3520)] == (380, 1) and got[(0, 256)] == (24, 1)
+    # mid-size chunks: one round of work-groups where that is the best plan measured (224 = 28 per XCD), two
+    # full rounds on every XCD where those were (9 pieces x 56 = 63 work-groups per XCD)
+    assert got[(5000, 1000)] == (224, 2) and got[(60000, 500)] == (504, 9)
     assert got[(6580, 40)][0] <= 256 and got[(6580, 40)][1] > 8
+    # no plan puts one work-group more than a whole number of rounds on an XCD's 32 compute units: 100 new
+    # tokens are 3 row tiles x 4 KV heads, and 21 pieces would put 33 work-groups on four of the XCDs
+    assert got[(60000, 100)] == (240, 20)
 
 
 def test_the_probe_is_not_the_product():
