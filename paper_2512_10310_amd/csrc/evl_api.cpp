@@ -420,14 +420,19 @@ static Chunking choose_chunking(int groups, int m_tiles) {
     return best;
 }
 
-// Work-groups entry i of a launch puts on each XCD: its chunks go round-robin over the 8 XCDs,
-// starting at XCD i % 8; the kernel recomputes the same assignment from (XCD, slot).
-static void add_xcd_load(int per_xcd[8], int i, int groups, int m_tiles, const Chunking &ck) {
+// Work-groups an entry of a launch puts on each XCD: its chunks go round-robin over the 8 XCDs,
+// starting at XCD *next, where the entry before it stopped; the kernel recomputes the same
+// assignment from (XCD, slot) and the entry's xcd_first.
+static void add_xcd_load(int per_xcd[8], int *next, evl::AttnSeq *q, int groups, int m_tiles, const Chunking &ck) {
     const int chunks = evl::xcd_chunks(groups, m_tiles, ck.rows, ck.pad);
+    q->chunk_rows = ck.rows;
+    q->chunk_pad = ck.pad;
+    q->xcd_first = *next;
     for (int x = 0; x < 8; ++x) {
-        const int r = (x - i) & 7;
+        const int r = (x - *next) & 7;
         per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * ck.rows;
     }
+    *next = (*next + chunks) & 7;
 }
 
 // Splitting buys balance and pays for it: more work-groups with their fixed cost, partial rows
@@ -516,6 +521,79 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
     }
     *tps_out = best_tps;
     return best_n;
+}
+
+// The same pricing for a launch that serves several sequences.  All sequences share one piece
+// length T (in key tiles), so that work-groups carry about the same amount of work whatever
+// their sequence's length; the candidates are the lengths that cut the longest sequence into
+// 1, 2, 3 ... pieces.  The chunks of the launch go round the XCDs entry after entry, so the
+// fullest XCD holds the launch's chunks / 8, rounded up, and its fullest shader engine a quarter
+// of that.  m_tiles, tiles, mean_see (key tiles a row tile of the sequence sees on average under
+// the causal mask), rows (token x head rows) per sequence.  Fills n_splits / tps per sequence;
+// returns the partial rows the plan needs.
+static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vector<int> &tiles,
+                                const std::vector<double> &mean_see, const std::vector<size_t> &rows, int n_kv_heads,
+                                size_t row_bytes, size_t capacity, std::vector<int> *n_splits, std::vector<int> *tps) {
+    const double kTile = 1.346, kTileFewRows = -0.169, kTileBusy = 0.187, kFixed = 5.825, kMerge = 10.0,
+                 kPerMB = 0.264, kTail = 0.325, kUnsplitMargin = 1.05;
+    const int n = (int)m_tiles.size();
+    const int longest_seq = *std::max_element(tiles.begin(), tiles.end());
+    std::vector<int> ns(n), len(n), best_ns(n, 1), best_len(tiles);
+    double best_t = 0.0, unsplit_t = 0.0;
+    size_t best_rows = 0;
+    std::vector<int> unsplit_len(tiles);
+    const int most = std::min<int>(kMaxSplits, std::max(1, longest_seq / kMinTilesPerSplit));
+    for (int want = 1; want <= most; want += want < 16 ? 1 : want / 4) {
+        const int T = std::max((longest_seq + want - 1) / want, want > 1 ? kMinTilesPerSplit : 1);
+        size_t ws_rows = 0;
+        double items = 0.0, work = 0.0, longest = 0.0, shortest = 1e30, rows_weighted = 0.0;
+        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, next = 0;
+        for (int i = 0; i < n; ++i) {
+            ns[i] = std::max(1, std::min(kMaxSplits, (tiles[i] + T - 1) / T));
+            len[i] = (tiles[i] + ns[i] - 1) / ns[i];
+            ns[i] = (tiles[i] + len[i] - 1) / len[i];
+            if (ns[i] > 1) ws_rows += (size_t)ns[i] * rows[i];
+            const int groups = ns[i] * n_kv_heads;
+            const Chunking ck = choose_chunking(groups, m_tiles[i]);
+            const int chunks = evl::xcd_chunks(groups, m_tiles[i], ck.rows, ck.pad);
+            for (int x = 0; x < 8; ++x) {
+                const int r = (x - next) & 7;
+                per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * ck.rows;
+            }
+            next = (next + chunks) & 7;
+            const double it = (double)m_tiles[i] * groups;
+            items += it;
+            work += mean_see[i] * m_tiles[i] * n_kv_heads;
+            rows_weighted += it * std::min(1.0, 6.0 / m_tiles[i]);
+            longest = std::max<double>(longest, std::min<double>(len[i], tiles[i]));
+            shortest = std::min<double>(shortest, mean_see[i] / ns[i]);
+        }
+        if (want > 1 && ws_rows == 0) break;             // pieces longer than every sequence: the unsplit plan again
+        if (ws_rows * row_bytes > capacity) continue;
+        const double mean = work / items, uniform = std::min(1.0, std::min(shortest, mean) / longest);
+        const double engine = (double)((*std::max_element(per_xcd, per_xcd + 8) + evl::kEnginesPerXcd - 1) /
+                                       evl::kEnginesPerXcd) / 8.0;
+        const double rounds = engine + (std::ceil(engine) - engine) * uniform;
+        const double tile_us = kTile + kTileFewRows * rows_weighted / items + kTileBusy * std::min(1.0, items / 256.0);
+        double t = std::max(longest * tile_us + kFixed,
+                            rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
+        if (ws_rows > 0) t += kMerge + kPerMB * (double)(ws_rows * row_bytes) * 1e-6;
+        if (want == 1) unsplit_t = t;
+        if (want == 1 || t < best_t) {
+            best_t = t;
+            best_ns = ns;
+            best_len = len;
+            best_rows = ws_rows;
+        }
+    }
+    if (best_rows > 0 && unsplit_t > 0.0 && unsplit_t <= kUnsplitMargin * best_t) {
+        best_ns.assign(n, 1);
+        best_len = unsplit_len;
+        best_rows = 0;
+    }
+    *n_splits = best_ns;
+    *tps = best_len;
+    return best_rows;
 }
 
 // Enqueue the attention kernel; when timing is switched on, an event pair takes the begin and
@@ -853,20 +931,9 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
         if (ws_rows * row_bytes <= partials_capacity(c) || ws_rows == 0) break;
         T *= 2;  // workspace too small: split less
     }
-    // with long chunks over short histories (a prefill) the split can cost more than it brings
-    if (!c->tuned && (ws_rows > 0 || n_seqs == 1)) {
-        double work = 0.0, longest = 0.0, longest_split = 0.0, items_split = 0.0, shortest = 1e30;
-        for (int i = 0; i < n_seqs; ++i) {
-            for (int mt = 0; mt < m_tiles[i]; ++mt) {  // key tiles row tile mt sees under the causal mask
-                const int last_tok = std::min((mt + 1) * MT, n_new[i] * G) - 1;
-                const int sees = (cache_lens[i] + last_tok / G + 1 + KN - 1) / KN;
-                work += (double)Hkv * sees;
-                shortest = std::min<double>(shortest, sees);
-            }
-            longest = std::max<double>(longest, tiles[i]);
-            longest_split = std::max<double>(longest_split, tps[i]);
-            items_split += (double)m_tiles[i] * Hkv * n_splits[i];
-        }
+    // unless the caller set a target, the plan is priced instead: how many pieces, if any (with long
+    // chunks over short histories -- a prefill -- a split costs more than it brings)
+    if (!c->tuned) {
         if (n_seqs == 1) {  // one set of rows: the number of pieces is searched, not derived from a target
             std::vector<int> see(m_tiles[0]);  // key tiles row tile mt sees under the causal mask
             for (int mt = 0; mt < m_tiles[0]; ++mt)
@@ -874,12 +941,18 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
             n_splits[0] = pick_pieces(see, Hkv, tiles[0], (size_t)n_new[0] * Hq, row_bytes,
                                       c->d.workspace ? partials_capacity(c) : 0, &tps[0]);
             ws_rows = n_splits[0] > 1 ? (size_t)n_splits[0] * n_new[0] * Hq : 0;
-        } else if (unsplit_wins(work, longest, (double)base_items, longest_split, items_split, ws_rows * row_bytes)) {
+        } else {  // several sequences: one piece length for all of them, priced the same way
+            std::vector<double> mean_see(n_seqs);
+            std::vector<size_t> rows(n_seqs);
             for (int i = 0; i < n_seqs; ++i) {
-                n_splits[i] = 1;
-                tps[i] = tiles[i];
+                double sum = 0.0;
+                for (int mt = 0; mt < m_tiles[i]; ++mt)
+                    sum += (cache_lens[i] + (std::min((mt + 1) * MT, n_new[i] * G) - 1) / G + 1 + KN - 1) / KN;
+                mean_see[i] = sum / std::max(m_tiles[i], 1);
+                rows[i] = (size_t)n_new[i] * Hq;
             }
-            ws_rows = 0;
+            ws_rows = pick_piece_length(m_tiles, tiles, mean_see, rows, Hkv, row_bytes,
+                                        c->d.workspace ? partials_capacity(c) : 0, &n_splits, &tps);
         }
     }
 
@@ -916,7 +989,7 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
         }
         attach_few(c, &p, few, &few_next);
         int items = 0, crow = 0, cseqs = 0;
-        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcd_next = 0;
         for (int i = 0; i < cnt; ++i) {
             const int k = order[base + i];
             const int64_t tok_off = tok_offs[k];
@@ -937,10 +1010,7 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
             q.part_off = (int64_t)part_off;
             q.q_pos = (int32_t)(c->pos0[seq_ids[k]] + cache_lens[k]);
             const int groups = n_splits[k] * Hkv;
-            const Chunking ck = choose_chunking(groups, m_tiles[k]);
-            q.chunk_rows = ck.rows;
-            q.chunk_pad = ck.pad;
-            add_xcd_load(per_xcd, i, groups, m_tiles[k], ck);
+            add_xcd_load(per_xcd, &xcd_next, &q, groups, m_tiles[k], choose_chunking(groups, m_tiles[k]));
             items += m_tiles[k] * groups;
             plan.max_splits = std::max(plan.max_splits, n_splits[k]);
             if (n_splits[k] > 1) {
@@ -1269,11 +1339,8 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
             q.total_splits = total_splits;
             q.part_off = 0;
         }
-        const Chunking ck = choose_chunking(g_splits[g] * Hkv, m_tiles);
-        p.seq[0].chunk_rows = ck.rows;
-        p.seq[0].chunk_pad = ck.pad;
-        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        add_xcd_load(per_xcd, 0, g_splits[g] * Hkv, m_tiles, ck);
+        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcd_next = 0;
+        add_xcd_load(per_xcd, &xcd_next, &p.seq[0], g_splits[g] * Hkv, m_tiles, choose_chunking(g_splits[g] * Hkv, m_tiles));
         p.n_items = m_tiles * g_splits[g] * Hkv;
         p.items_per_xcd = *std::max_element(per_xcd, per_xcd + 8);
         plan.n_items += p.n_items;
@@ -1488,7 +1555,7 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
         p.multi_entry = 1;
         attach_few(c, &p, few, &few_next);
         int items = 0, crow = 0, cseqs = 0, at = 0;
-        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcd_next = 0;
         for (int g = g0; g < g1; ++g) {
             const Group &gr = grp[g];
             for (int i = 0; i < gr.count; ++i) {
@@ -1510,10 +1577,8 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
                 q.total_splits = gr.n_splits;
                 q.part_off = (int64_t)part_off;
             }
-            const Chunking ck = choose_chunking(gr.n_splits * Hkv, gr.m_tiles);
-            p.seq[at].chunk_rows = ck.rows;
-            p.seq[at].chunk_pad = ck.pad;
-            add_xcd_load(per_xcd, at, gr.n_splits * Hkv, gr.m_tiles, ck);
+            add_xcd_load(per_xcd, &xcd_next, &p.seq[at], gr.n_splits * Hkv, gr.m_tiles,
+                         choose_chunking(gr.n_splits * Hkv, gr.m_tiles));
             items += gr.m_tiles * gr.n_splits * Hkv;
             plan.max_splits = std::max(plan.max_splits, gr.n_splits);
             if (gr.n_splits > 1) {

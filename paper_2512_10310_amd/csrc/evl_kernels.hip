@@ -605,16 +605,17 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     // are cut into chunks of chunk_rows items (group by group, or all groups end to end: the
     // host's choice per entry); the row tiles of one group read the same K/V, so a chunk takes
     // consecutive slots of one XCD -- chunks of at most kXcdChunkRowTiles items, so that a group
-    // of many row tiles (a long prefill) is not pinned to one XCD; the chunks of entry i go
-    // round-robin over the XCDs starting at XCD i % 8, which spreads every sequence -- long or
-    // short -- over the whole chip.  Sequences are listed longest first.
+    // of many row tiles (a long prefill) is not pinned to one XCD; the chunks of the launch go
+    // round the XCDs entry after entry (an entry's first chunk to XCD xcd_first, where the entry
+    // before it stopped), which spreads every sequence -- long or short -- over the whole chip
+    // and loads the XCDs evenly to within one chunk.  Sequences are listed longest first.
     const int G = p.group, Hq = p.n_q_heads, Hkv = p.n_kv_heads;
     const int xcd = blockIdx.x % 8;
     int local = blockIdx.x / 8;
     int s = -1, gs = 0;
     if (p.n_seqs <= 4) {  // a few entries: a scalar walk is the shortest
         for (int e = 0; e < p.n_seqs; ++e) {
-            const int r = (xcd - e) & 7;  // first chunk of entry e that lands on this XCD
+            const int r = (xcd - p.seq[e].xcd_first) & 7;  // first chunk of entry e that lands on this XCD
             const int mtl = max(p.seq[e].chunk_rows, 1);
             const int chunks = xcd_chunks(p.seq[e].n_splits * Hkv, p.seq[e].m_tiles, p.seq[e].chunk_rows, p.seq[e].chunk_pad);
             const int here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
@@ -636,7 +637,7 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
         if (e < p.n_seqs) {
             const int chunks = xcd_chunks(p.seq[e].n_splits * Hkv, p.seq[e].m_tiles, p.seq[e].chunk_rows, p.seq[e].chunk_pad);
             mtl = max(p.seq[e].chunk_rows, 1);
-            r = (xcd - e) & 7;  // first chunk of entry e that lands on this XCD
+            r = (xcd - p.seq[e].xcd_first) & 7;  // first chunk of entry e that lands on this XCD
             here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
         }
         int incl = here;

@@ -148,7 +148,7 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
     const int G = p.group, Hq = p.n_q_heads, Hkv = p.n_kv_heads, KN = kKeyTile;
     REQUIRE(p.n_seqs >= 1 && p.n_seqs <= kMaxEntries, "%s: n_seqs %d", who, p.n_seqs);
     const size_t ws_rows = partial_rows(p.part_o, p.part_ml, D, p.out_f32 != 0);
-    int items = 0, per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int items = 0, per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcd_next = 0;
     bool multi = false;
     for (int e = 0; e < p.n_seqs;) {
         const AttnSeq &sq = p.seq[e];
@@ -213,10 +213,13 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
                 "%s: entry %d: padded chunks of %d slots do not keep the shader engines in step", who, e, chunk_rows);
         const int chunks = sq.chunk_pad ? groups * ((sq.m_tiles + chunk_rows - 1) / chunk_rows)
                                         : (groups * sq.m_tiles + chunk_rows - 1) / chunk_rows;
+        REQUIRE(sq.xcd_first == xcd_next, "%s: entry %d: first chunk on XCD %d, the entry before it stopped at %d", who, e,
+                sq.xcd_first, xcd_next);
         for (int x = 0; x < 8; ++x) {
-            const int r = (x - e) & 7;
+            const int r = (x - sq.xcd_first) & 7;
             per_xcd[x] += (chunks > r ? (chunks - r + 7) / 8 : 0) * chunk_rows;
         }
+        xcd_next = (xcd_next + chunks) & 7;
         items += groups * sq.m_tiles;
         e += sq.n_ent;
     }
@@ -231,7 +234,7 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
             int local = b / 8, s = -1, gs = 0;
             for (int e = 0; e < p.n_seqs; ++e) {
                 const AttnSeq &en = p.seq[e];
-                const int r = (xcd - e) & 7, mtl = en.chunk_rows > 1 ? en.chunk_rows : 1;
+                const int r = (xcd - en.xcd_first) & 7, mtl = en.chunk_rows > 1 ? en.chunk_rows : 1;
                 const int chunks = xcd_chunks(en.n_splits * Hkv, en.m_tiles, en.chunk_rows, en.chunk_pad);
                 const int here = (chunks > r ? (chunks - r + 7) / 8 : 0) * mtl;
                 if (local < here) {
