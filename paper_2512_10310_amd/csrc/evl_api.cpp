@@ -435,25 +435,9 @@ static void add_xcd_load(int per_xcd[8], int *next, evl::AttnSeq *q, int groups,
     *next = (*next + chunks) & 7;
 }
 
-// Splitting buys balance and pays for it: more work-groups with their fixed cost, partial rows
-// written and read back, one more kernel.  With long chunks over short histories (a prefill:
-// thousands of rows, each split a full copy of them) the price is the larger part, so the two
-// plans of a launch are priced with a coarse model and the split is dropped if it loses.
-// Arguments: key tiles over all work items, key tiles of the longest work item and number of
-// work items without the split; the last two and the partial bytes with it.  Times in
-// microseconds: a key tile of a work-group, a work-group's start and end, HBM bytes per
-// microsecond, the merge kernel's launch; CUs; the share of the longest work-group that is left
-// hanging at the end.  (Chunks over long histories are never close: 201 against 43 for the
-// 204-token step over 6580 cached tokens.)
-static bool unsplit_wins(double work_tiles, double longest, double items, double longest_split, double items_split,
-                         size_t partial_bytes) {
-    const double kTile = 1.9, kFixed = 7.0, kBytesPerUs = 4.0e6, kMerge = 5.0, kCus = 256.0, kTail = 0.25;
-    const double whole = std::max(longest, work_tiles / kCus + kTail * longest) * kTile + items / kCus * kFixed;
-    const double split = std::max(longest_split, work_tiles / kCus + kTail * longest_split) * kTile +
-                         items_split / kCus * kFixed + 2.0 * (double)partial_bytes / kBytesPerUs + kMerge;
-    return whole <= split;
-}
-
+// Splitting a key range buys balance and pays for it: more work-groups with their fixed cost,
+// partial rows written and read back, one more kernel.  With long chunks over short histories (a
+// prefill: thousands of rows, each piece a full copy of them) the price is the larger part.
 // Number of pieces for a launch that serves ONE set of rows (one sequence's chunk): every
 // candidate is priced with a model of how the chip runs the launch, fitted to timings of forced
 // plans over a grid of history and chunk lengths (8 histories from 0 to 60 000 tokens, 15 chunk
@@ -503,7 +487,8 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
         const double busy = std::min(1.0, (double)(live * n_kv_heads) / 256.0);
         // work-groups on the fullest shader engine, in rounds of its 8 compute units
         const double engine = (double)choose_chunking((int)n * n_kv_heads, m_tiles).engine / 8.0;
-        const double rounds = engine + (std::ceil(engine) - engine) * uniform;
+        // (whole rounds matter for the first two; with many rounds the in-order dispatch evens the end out)
+        const double rounds = engine + (std::ceil(engine) - engine) * uniform * std::min(1.0, 2.0 / engine);
         const double tile_us = kTile + kTileFewRows * std::min(1.0, 6.0 / m_tiles) + kTileBusy * busy;
         double t = std::max(longest * tile_us + kFixed,
                             rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
@@ -573,7 +558,8 @@ static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vect
         const double mean = work / items, uniform = std::min(1.0, std::min(shortest, mean) / longest);
         const double engine = (double)((*std::max_element(per_xcd, per_xcd + 8) + evl::kEnginesPerXcd - 1) /
                                        evl::kEnginesPerXcd) / 8.0;
-        const double rounds = engine + (std::ceil(engine) - engine) * uniform;
+        // (whole rounds matter for the first two; with many rounds the in-order dispatch evens the end out)
+        const double rounds = engine + (std::ceil(engine) - engine) * uniform * std::min(1.0, 2.0 / engine);
         const double tile_us = kTile + kTileFewRows * rows_weighted / items + kTileBusy * std::min(1.0, items / 256.0);
         double t = std::max(longest * tile_us + kFixed,
                             rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
@@ -1522,19 +1508,21 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
         if (ws_rows * row_bytes <= partials_capacity(c) || ws_rows == 0) break;
         T *= 2;
     }
-    if (ws_rows > 0 && !c->tuned) {  // a pack of long chunks over short histories: see unsplit_wins
-        double longest = 0.0, longest_split = 0.0, items_split = 0.0;
-        for (const Group &g : grp) {
-            longest = std::max<double>(longest, (double)g.tiles);
-            longest_split = std::max<double>(longest_split, g.tps);
-            items_split += (double)g.m_tiles * Hkv * g.n_splits;
+    if (!c->tuned) {  // no target set by the caller: the common piece length is priced, as in the plain batched call
+        std::vector<int> g_m(n_groups), g_tiles(n_groups), g_ns, g_tps;
+        std::vector<double> g_see(n_groups);
+        std::vector<size_t> g_rows(n_groups);
+        for (int g = 0; g < n_groups; ++g) {
+            g_m[g] = grp[g].m_tiles;
+            g_tiles[g] = (int)grp[g].tiles;
+            g_see[g] = (double)grp[g].tiles;  // (the causal cut inside the chunk's own entry is not counted)
+            g_rows[g] = (size_t)n_new[g] * Hq;
         }
-        if (unsplit_wins((double)work, longest, (double)base_items, longest_split, items_split, ws_rows * row_bytes)) {
-            for (Group &g : grp) {
-                g.n_splits = 1;
-                g.tps = (int)g.tiles;
-            }
-            ws_rows = 0;
+        ws_rows = pick_piece_length(g_m, g_tiles, g_see, g_rows, Hkv, row_bytes,
+                                    c->d.workspace ? partials_capacity(c) : 0, &g_ns, &g_tps);
+        for (int g = 0; g < n_groups; ++g) {
+            grp[g].n_splits = g_ns[g];
+            grp[g].tps = g_tps[g];
         }
     }
     void *part_o = c->d.workspace;
