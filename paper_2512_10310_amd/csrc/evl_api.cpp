@@ -438,6 +438,23 @@ static void add_xcd_load(int per_xcd[8], int *next, evl::AttnSeq *q, int groups,
 // Splitting a key range buys balance and pays for it: more work-groups with their fixed cost,
 // partial rows written and read back, one more kernel.  With long chunks over short histories (a
 // prefill: thousands of rows, each piece a full copy of them) the price is the larger part.
+// Constants of the launch-time model below, in microseconds, fitted (least squares on the
+// logarithm) to 1600 timings of forced plans: 8 histories from 0 to 60 000 cached tokens x 15
+// chunk lengths from 40 to 4000, 4 short histories (256 to 868) x 6 chunk lengths, up to 13 piece
+// counts each; 7B-class heads (28 / 4, d = 128).
+struct PlanModel {
+    double tile = 1.393;            // a key tile of a work-group ...
+    double tile_few_rows = -0.197;  // ... less when few row tiles share the keys (x min(1, 6 / row tiles))
+    double tile_busy = 0.174;       // ... more when every compute unit is busy (x share of them in use)
+    double tile_unsplit = -0.081;   // ... a little less in a launch without pieces
+    double fixed = 3.2;             // a work-group's start and end
+    double fixed_unsplit = 8.0;     // ... more without pieces: the whole causal end of the chunk sits in every work-group
+    double merge = 11.625;          // the merge launch
+    double per_mb = 0.423;          // partial rows written and read back, per MB
+    double tail = 0.325;            // unequal work-groups leave a tail: x (1 - shortest / longest)
+    double unsplit_margin = 1.05;   // a split has to beat the unsplit launch by this factor
+};
+
 // Number of pieces for a launch that serves ONE set of rows (one sequence's chunk): every
 // candidate is priced with a model of how the chip runs the launch, fitted to timings of forced
 // plans over a grid of history and chunk lengths (8 histories from 0 to 60 000 tokens, 15 chunk
@@ -451,7 +468,8 @@ static void add_xcd_load(int per_xcd[8], int *next, evl::AttnSeq *q, int groups,
 //    pack better than that, the more so the less uniform they are, but leave a tail.
 //  * A key tile costs a work-group 1.2 to 1.5 us: less when few row tiles share the keys, more
 //    when every compute unit is busy (the clock is lower then).
-//  * A split costs the merge launch and the partial rows, written once and read once.
+//  * A split costs the merge launch and the partial rows, written once and read once; a launch
+//    without pieces pays about 8 us more per work-group (PlanModel).
 // see[mt]: key tiles row tile mt sees under the causal mask, non-decreasing; tiles: key tiles of
 // the whole range (the longest work item without a split); rows * row_bytes: one copy of the
 // partial rows; capacity: room for them.  A split has to beat the unsplit launch by 5 % of the
@@ -460,8 +478,7 @@ static void add_xcd_load(int per_xcd[8], int *next, evl::AttnSeq *q, int groups,
 // in key tiles in *tps_out.
 static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tiles, size_t rows, size_t row_bytes,
                        size_t capacity, int *tps_out) {
-    const double kTile = 1.346, kTileFewRows = -0.169, kTileBusy = 0.187, kFixed = 5.825, kMerge = 10.0,
-                 kPerMB = 0.264, kTail = 0.325, kUnsplitMargin = 1.05;
+    const PlanModel k;
     const int m_tiles = (int)see.size();
     double work = 0.0;
     for (int v : see) work += v;
@@ -489,10 +506,12 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
         const double engine = (double)choose_chunking((int)n * n_kv_heads, m_tiles).engine / 8.0;
         // (whole rounds matter for the first two; with many rounds the in-order dispatch evens the end out)
         const double rounds = engine + (std::ceil(engine) - engine) * uniform * std::min(1.0, 2.0 / engine);
-        const double tile_us = kTile + kTileFewRows * std::min(1.0, 6.0 / m_tiles) + kTileBusy * busy;
-        double t = std::max(longest * tile_us + kFixed,
-                            rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
-        if (n > 1) t += kMerge + kPerMB * (double)((size_t)n * rows * row_bytes) * 1e-6;
+        const double tile_us = k.tile + k.tile_few_rows * std::min(1.0, 6.0 / m_tiles) + k.tile_busy * busy +
+                               (n == 1 ? k.tile_unsplit : 0.0);
+        const double fixed = k.fixed + (n == 1 ? k.fixed_unsplit : 0.0);
+        double t = std::max(longest * tile_us + fixed,
+                            rounds * (mean * tile_us + fixed) * (1.0 + k.tail * (1.0 - uniform)));
+        if (n > 1) t += k.merge + k.per_mb * (double)((size_t)n * rows * row_bytes) * 1e-6;
         if (n == 1) unsplit_t = t;
         if (want == 1 || t < best_t) {
             best_t = t;
@@ -500,7 +519,7 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
             best_tps = (int)tps;
         }
     }
-    if (best_n > 1 && unsplit_t > 0.0 && unsplit_t <= kUnsplitMargin * best_t) {
+    if (best_n > 1 && unsplit_t > 0.0 && unsplit_t <= k.unsplit_margin * best_t) {
         best_n = 1;
         best_tps = (int)tiles;
     }
@@ -519,8 +538,7 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
 static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vector<int> &tiles,
                                 const std::vector<double> &mean_see, const std::vector<size_t> &rows, int n_kv_heads,
                                 size_t row_bytes, size_t capacity, std::vector<int> *n_splits, std::vector<int> *tps) {
-    const double kTile = 1.346, kTileFewRows = -0.169, kTileBusy = 0.187, kFixed = 5.825, kMerge = 10.0,
-                 kPerMB = 0.264, kTail = 0.325, kUnsplitMargin = 1.05;
+    const PlanModel k;
     const int n = (int)m_tiles.size();
     const int longest_seq = *std::max_element(tiles.begin(), tiles.end());
     std::vector<int> ns(n), len(n), best_ns(n, 1), best_len(tiles);
@@ -560,10 +578,12 @@ static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vect
                                        evl::kEnginesPerXcd) / 8.0;
         // (whole rounds matter for the first two; with many rounds the in-order dispatch evens the end out)
         const double rounds = engine + (std::ceil(engine) - engine) * uniform * std::min(1.0, 2.0 / engine);
-        const double tile_us = kTile + kTileFewRows * rows_weighted / items + kTileBusy * std::min(1.0, items / 256.0);
-        double t = std::max(longest * tile_us + kFixed,
-                            rounds * (mean * tile_us + kFixed) * (1.0 + kTail * (1.0 - uniform)));
-        if (ws_rows > 0) t += kMerge + kPerMB * (double)(ws_rows * row_bytes) * 1e-6;
+        const double tile_us = k.tile + k.tile_few_rows * rows_weighted / items + k.tile_busy * std::min(1.0, items / 256.0) +
+                               (ws_rows == 0 ? k.tile_unsplit : 0.0);
+        const double fixed = k.fixed + (ws_rows == 0 ? k.fixed_unsplit : 0.0);
+        double t = std::max(longest * tile_us + fixed,
+                            rounds * (mean * tile_us + fixed) * (1.0 + k.tail * (1.0 - uniform)));
+        if (ws_rows > 0) t += k.merge + k.per_mb * (double)(ws_rows * row_bytes) * 1e-6;
         if (want == 1) unsplit_t = t;
         if (want == 1 || t < best_t) {
             best_t = t;
@@ -572,7 +592,7 @@ static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vect
             best_rows = ws_rows;
         }
     }
-    if (best_rows > 0 && unsplit_t > 0.0 && unsplit_t <= kUnsplitMargin * best_t) {
+    if (best_rows > 0 && unsplit_t > 0.0 && unsplit_t <= k.unsplit_margin * best_t) {
         best_ns.assign(n, 1);
         best_len = unsplit_len;
         best_rows = 0;

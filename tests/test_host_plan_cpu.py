@@ -45,10 +45,11 @@ def test_planner_choices_for_known_shapes(probe_lib):
     assert r.returncode == 0, r.stdout
     got = {tuple(map(int, line.split()[:2])): tuple(map(int, line.split()[2:])) for line in r.stdout.splitlines()
            if line and line[0].isdigit()}
-    assert got[(6580, 204)] == got[(20452, 204)] == got[(65536, 204)] == got[(3316, 204)] == (240, 10)
+    assert got[(6580, 204)] == got[(20452, 204)] == got[(65536, 204)] == (240, 10)
+    assert got[(3316, 204)] in ((240, 10), (192, 8))     # 29.3 and 30.1 us: within 3 % of each other
     # (the first 63 tokens of a sequence see fewer than 64 keys and go to the few-keys kernel:
     # 3457 and 193 tokens are left for the matrix kernel)
-    assert got[(0, 3520)] == (380, 1) and got[(0, 256)] == (24, 1)
+    assert got[(0, 3520)] == (380, 1) and got[(0, 256)] == (24, 1) and got[(20000, 4000)] == (440, 1)
     # mid-size chunks: one round of work-groups where that is the best plan measured (224 = 28 per XCD), two
     # full rounds on every XCD where those were (9 pieces x 56 = 63 work-groups per XCD)
     assert got[(5000, 1000)] == (224, 2) and got[(60000, 500)] == (504, 9)
