@@ -410,6 +410,15 @@ def main():
             "algorithmic_GBps": round((sum(2 * (c_ + n) * Hkv * d * 2 for c_ in lens) + 16 * 2 * n * Hq * d * 2)
                                       / (ms3 * 1e-3) / 1e9, 1),
             "plan": c3.last_plan()}
+        # small batches of the same cache: the first 2, 4 and 8 episodes in one launch (attention + merge only)
+        small = []
+        for S in (2, 4, 8):
+            sub, sub_lens = ids[:S], lens[:S]
+            ms_s = timed_ms(lambda: c3.chunk_attention_batched(q3[:S * n], sub, sub_lens, [n] * S, out3[:S * n]), 20, calls=3)
+            fl_s = sum(attention_flops(Hq, d, c_, n) for c_ in sub_lens)
+            small.append({"episodes": S, "cached_tokens": sub_lens, "ms": round(ms_s, 4),
+                          "attention_TFLOPs": round(fl_s / (ms_s * 1e-3) / 1e12, 1), "plan": c3.last_plan()[:2]})
+        result["ragged_batch"]["small_batches"] = small
         del c3, k_pool, v_pool, ws3, q3, k3, v3, out3
 
         # redundancy: re-prefill of a 16-frame window every step vs cache reuse of one chunk
