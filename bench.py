@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0
 # by construction ("traffic_modelled": K and V once, the queries once per piece of the key
 # range, the partial rows of every piece), which cannot go stale.
 ATTN_TRAFFIC_BYTES_PER_LAUNCH = 41.36e6
-ATTN_TRAFFIC_MEASURED_ON_SHA1 = "d8b487274a6c178ddfc770864c1ca2f3b1ea8d84"
+ATTN_TRAFFIC_MEASURED_ON_SHA1 = "ce17f7f87807851d973de5469805419217037104"
 KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_10310_amd", "csrc",
                              "evl_kernels.hip")
 

@@ -69,7 +69,7 @@ struct AttnSeq {
     int32_t chunk_rows;       // attention kernel: work items per XCD chunk (first entry of a group), ...
     int32_t chunk_pad;        // ... and 1 if every (KV head, piece) group is cut and padded by itself
     int32_t xcd_first;        // ... and the XCD its first chunk goes to (the launch's chunks go round the XCDs entry after entry)
-    int32_t pad_;
+    int32_t tile_major;       // ... and 1 if the dense cut counts items row tile after row tile (all groups' longest first)
     int64_t part_off;         // first partial row of the rows' block in the workspace
 };
 

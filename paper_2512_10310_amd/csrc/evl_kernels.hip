@@ -674,8 +674,14 @@ __global__ __launch_bounds__(kRowsPerWorkgroup / (32 * QB) * 64) void attn_kerne
     } else {
         const int u = gs * mtl + local % mtl;
         if (u >= sq.n_splits * Hkv * sq.m_tiles) return;  // padding of the entry's last chunk
-        grp = u / sq.m_tiles;
-        mt_up = u - grp * sq.m_tiles;
+        if (sq.tile_major) {  // row tile after row tile: the groups' longest work items come first
+            const int groups = sq.n_splits * Hkv;
+            mt_up = u / groups;
+            grp = u - mt_up * groups;
+        } else {
+            grp = u / sq.m_tiles;
+            mt_up = u - grp * sq.m_tiles;
+        }
     }
     // last row tile first: under the causal mask it sees the most keys, and the longest
     // work-groups should not be the ones that start last

@@ -209,6 +209,8 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
         const int chunk_rows = sq.chunk_rows;
         REQUIRE(chunk_rows >= 1 && chunk_rows <= kXcdChunkRowTiles && (sq.chunk_pad == 0 || sq.chunk_pad == 1),
                 "%s: entry %d: chunks of %d work items, pad flag %d", who, e, chunk_rows, sq.chunk_pad);
+        REQUIRE((sq.tile_major == 0 || sq.tile_major == 1) && !(sq.tile_major && sq.chunk_pad),
+                "%s: entry %d: row-tile-major order needs the dense cut (flags %d, %d)", who, e, sq.tile_major, sq.chunk_pad);
         REQUIRE(!sq.chunk_pad || chunk_rows % kEnginesPerXcd == 0,
                 "%s: entry %d: padded chunks of %d slots do not keep the shader engines in step", who, e, chunk_rows);
         const int chunks = sq.chunk_pad ? groups * ((sq.m_tiles + chunk_rows - 1) / chunk_rows)
@@ -256,8 +258,13 @@ hipError_t launch_chunk_attention(const AttnParams &p, int D, hipStream_t, hipEv
             } else {
                 const int u = gs * mtl + local % mtl;
                 if (u >= sq.n_splits * Hkv * sq.m_tiles) continue;
-                grp = u / sq.m_tiles;
-                mt_up = u - grp * sq.m_tiles;
+                if (sq.tile_major) {
+                    mt_up = u / (sq.n_splits * Hkv);
+                    grp = u - mt_up * (sq.n_splits * Hkv);
+                } else {
+                    grp = u / sq.m_tiles;
+                    mt_up = u - grp * sq.m_tiles;
+                }
             }
             REQUIRE(grp >= 0 && grp < sq.n_splits * Hkv, "%s: work-group %d lands in group %d of entry %d", who, b, grp, s);
             char &mark = seen[s][(size_t)grp * sq.m_tiles + mt_up];
