@@ -398,26 +398,37 @@ static int engine_load(int groups, int m_tiles, int rows, int pad) {
 }
 
 // The cut for an entry: groups of at most kXcdChunkRowTiles row tiles are chunks by themselves.
-// Otherwise the candidates are chunks of 8 cut group by group with padding, chunks of a divisor
-// of m_tiles between 4 and 7 (dense, no padding, no straddling), and chunks of 8 cut densely
-// (straddling groups); the one that needs the fewest rounds of work-groups on the fullest shader
-// engine wins, ties going to them in that order, larger divisors first -- the order measured for
-// launches of many rounds (a 4000-token prefill: 138 us padded, 147 us dense by 8, 153 us by 5).
+// Otherwise the candidates are, in order of preference, chunks of 8 cut group by group with
+// padding, dense chunks of a divisor of m_tiles between 7 and 4 (no padding, no straddling),
+// and dense chunks of 8 down to 4 that straddle groups.  What decides is the load of the fullest
+// shader engine: first its rounds of 8 work-groups, then -- work-groups that run at the same
+// time share their XCD's L2 and clock -- the load itself (220 equal work-groups in one round:
+// 263 us with 32 on the fullest XCD, 250 with 30, 240 to 247 with 28); candidates within 3 % of
+// the lightest count as equal and the preferred one of them is taken (a 4000-token prefill in
+// many rounds: 138 us padded, 147 us dense by 8, 153 us by 5).
 static Chunking choose_chunking(int groups, int m_tiles) {
     const int cus = evl::kCusPerXcd / evl::kEnginesPerXcd;
     if (m_tiles <= evl::kXcdChunkRowTiles) {
         const int rows = std::max(m_tiles, 1);
         return Chunking{rows, 0, engine_load(groups, m_tiles, rows, 0)};
     }
-    Chunking best{evl::kXcdChunkRowTiles, 1, engine_load(groups, m_tiles, evl::kXcdChunkRowTiles, 1)};
-    auto consider = [&](int rows, int pad) {
-        const int e = engine_load(groups, m_tiles, rows, pad);
-        if ((e + cus - 1) / cus < (best.engine + cus - 1) / cus) best = Chunking{rows, pad, e};
-    };
+    Chunking cand[1 + 2 * (evl::kXcdChunkRowTiles / 2 + 1)];
+    int n = 0;
+    cand[n++] = Chunking{evl::kXcdChunkRowTiles, 1, 0};
     for (int rows = evl::kXcdChunkRowTiles - 1; rows >= evl::kXcdChunkRowTiles / 2; --rows)
-        if (m_tiles % rows == 0) consider(rows, 0);
-    consider(evl::kXcdChunkRowTiles, 0);
-    return best;
+        if (m_tiles % rows == 0) cand[n++] = Chunking{rows, 0, 0};
+    for (int rows = evl::kXcdChunkRowTiles; rows >= evl::kXcdChunkRowTiles / 2; --rows)
+        if (m_tiles % rows != 0) cand[n++] = Chunking{rows, 0, 0};
+    int lightest = 0;
+    for (int i = 0; i < n; ++i) {
+        cand[i].engine = engine_load(groups, m_tiles, cand[i].rows, cand[i].pad);
+        if (cand[i].engine < cand[lightest].engine) lightest = i;
+    }
+    const int rounds = (cand[lightest].engine + cus - 1) / cus;
+    for (int i = 0; i < n; ++i)
+        if ((cand[i].engine + cus - 1) / cus == rounds && cand[i].engine * 100 <= cand[lightest].engine * 103)
+            return cand[i];
+    return cand[lightest];
 }
 
 // An unsplit entry with more work items than compute units -- a long chunk whose row tiles see
