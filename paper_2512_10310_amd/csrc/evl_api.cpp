@@ -30,6 +30,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // Work-groups the attention launch aims for: enough to give each of the 256 CUs a few.
 constexpr int kDefaultTargetItems = 240;
 constexpr int kMinTilesPerSplit = 4;   // 256 keys: below this the prologue dominates
+constexpr int kDecodeTargetGroups = 140;  // work-groups a launch of the short-chunk kernel aims at
 constexpr int kMaxSplits = 256;  // pieces of one key range (a single long sequence can fill the chip by itself)
 
 struct Plan {
@@ -749,8 +750,11 @@ static evl_status decode_attention(evl_cache *c, const void *q_new, void *out,
         tiles[i] = (ents[i].k_stop + KT - 1) / KT - ents[i].k_begin / KT;
         all_tiles += tiles[i];
     }
-    // one piece length for the launch: about one piece per wave the chip holds at a time
-    const int64_t target = (int64_t)c->target_items * W;
+    // one piece length for the launch: about 140 work-groups of W pieces unless the caller set a target
+    // (timed over 3520 / 20 656 / 65 536 cached tokens, 1 and 4 new: 110 to 150 work-groups are the
+    // fastest everywhere -- 240, one per compute unit, cost 4 to 13 % more at the two longer histories,
+    // more work-groups than that 20 to 35 %, 60 or fewer 15 to 60 %)
+    const int64_t target = (int64_t)(c->tuned ? c->target_items : kDecodeTargetGroups) * W;
     // short histories (up to 64 work-groups' worth of single tiles): one tile per wave, so that the
     // few compute units in use pull less each; beyond that two tiles per piece keep the merge small
     const int64_t min_tiles = all_tiles * Hkv <= 64 * W ? 1 : kMinDecodeTilesPerPiece;
@@ -777,6 +781,31 @@ static evl_status decode_attention(evl_cache *c, const void *q_new, void *out,
         if (counters_of(c) && ws_rows * row_bytes <= partials_capacity(c)) break;
         T *= 2;  // no room for the partial results (or for the counters): fewer, longer pieces
         if (T > (int64_t)1 << 40) return EVL_OK;
+    }
+    // A group's pieces are dealt to work-groups of W waves: with 9 pieces two work-groups would run
+    // with 7 idle waves.  The group's pieces are made shorter until its work-groups are full (the
+    // number of work-groups, and with it the partial rows, stays as it is).
+    for (int g = 0; g < n_groups; ++g) {
+        const int64_t budget = (int64_t)wgs[g] * W;
+        auto pieces_at = [&](int64_t len) {
+            int64_t np = 0;
+            for (int i = first[g]; i < first[g + 1]; ++i) np += std::max<int64_t>(1, (tiles[i] + len - 1) / len);
+            return np;
+        };
+        int64_t lo = min_tiles, hi = T;  // the shortest piece length whose pieces still fit the work-groups
+        if (pieces_at(hi) > budget) continue;  // (pieces were counted after rounding: leave the group alone)
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) / 2;
+            if (pieces_at(mid) <= budget)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        for (int i = first[g]; i < first[g + 1]; ++i) {
+            const int n = (int)std::max<int64_t>(1, (tiles[i] + hi - 1) / hi);
+            tps[i] = (tiles[i] + n - 1) / n;
+            pieces[i] = (tiles[i] + tps[i] - 1) / tps[i];
+        }
     }
     if (ws_rows > 0) {
         evl_status st = ready_counters(c);
