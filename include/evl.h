@@ -332,8 +332,11 @@ evl_status evl_last_plan(const evl_cache *cache, int32_t *n_workgroups, int32_t 
 /*
  * Tuning knob of the attention launch: target_workgroups is the number of work-groups the
  * key-range splitting aims for; the split it leads to is then made as asked.  0 returns to the
- * default, in which the library also decides whether a launch is better off without a split (a
- * long chunk over a short history).  Results do not depend on it beyond rounding order.
+ * default, in which the library prices the candidate piece counts of every launch with a model of
+ * the chip (how work-groups are dealt to XCDs and shader engines, what a key tile, a work-group's
+ * start and end and the merge of the pieces cost) and takes the cheapest, which may be no split at
+ * all (a long chunk over a short history); launches of the short-chunk kernel aim at about 140
+ * work-groups.  Results do not depend on it beyond rounding order.
  */
 evl_status evl_cache_tune(evl_cache *cache, int32_t target_workgroups);
 
