@@ -476,6 +476,16 @@ struct PlanModel {
     double tail = 0.325;            // unequal work-groups leave a tail: x (1 - shortest / longest)
     double tail_longest_first = 0.5;  // ... a smaller one when the longest are dealt first (tile_major_pays)
     double unsplit_margin = 1.05;   // a split has to beat the unsplit launch by this factor
+    // Heads of 64 channels: a key tile is about this fraction of the work (not fitted: set so that the
+    // choices for 16 / 4 heads of 64 channels come out within a few percent of the best forced plans)
+    explicit PlanModel(int head_dim) {
+        const double scale = head_dim == 64 ? kTileScaleD64 : 1.0;
+        tile *= scale;
+        tile_few_rows *= scale;
+        tile_busy *= scale;
+        tile_unsplit *= scale;
+    }
+    static constexpr double kTileScaleD64 = 0.5;
 };
 
 // Number of pieces for a launch that serves ONE set of rows (one sequence's chunk): every
@@ -499,9 +509,9 @@ struct PlanModel {
 // model's time to be taken (where the two are close the model errs towards splitting, and the
 // unsplit launch needs no workspace).  Returns the number of pieces (1 = no split), their length
 // in key tiles in *tps_out.
-static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tiles, size_t rows, size_t row_bytes,
-                       size_t capacity, int *tps_out) {
-    const PlanModel k;
+static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int head_dim, int64_t tiles, size_t rows,
+                       size_t row_bytes, size_t capacity, int *tps_out) {
+    const PlanModel k(head_dim);
     const int m_tiles = (int)see.size();
     double work = 0.0;
     for (int v : see) work += v;
@@ -563,8 +573,8 @@ static int pick_pieces(const std::vector<int> &see, int n_kv_heads, int64_t tile
 // returns the partial rows the plan needs.
 static size_t pick_piece_length(const std::vector<int> &m_tiles, const std::vector<int> &tiles,
                                 const std::vector<double> &mean_see, const std::vector<size_t> &rows, int n_kv_heads,
-                                size_t row_bytes, size_t capacity, std::vector<int> *n_splits, std::vector<int> *tps) {
-    const PlanModel k;
+                                int head_dim, size_t row_bytes, size_t capacity, std::vector<int> *n_splits, std::vector<int> *tps) {
+    const PlanModel k(head_dim);
     const int n = (int)m_tiles.size();
     const int longest_seq = *std::max_element(tiles.begin(), tiles.end());
     std::vector<int> ns(n), len(n), best_ns(n, 1), best_len(tiles);
@@ -998,7 +1008,7 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
             std::vector<int> see(m_tiles[0]);  // key tiles row tile mt sees under the causal mask
             for (int mt = 0; mt < m_tiles[0]; ++mt)
                 see[mt] = (cache_lens[0] + (std::min((mt + 1) * MT, n_new[0] * G) - 1) / G + 1 + KN - 1) / KN;
-            n_splits[0] = pick_pieces(see, Hkv, tiles[0], (size_t)n_new[0] * Hq, row_bytes,
+            n_splits[0] = pick_pieces(see, Hkv, D, tiles[0], (size_t)n_new[0] * Hq, row_bytes,
                                       c->d.workspace ? partials_capacity(c) : 0, &tps[0]);
             ws_rows = n_splits[0] > 1 ? (size_t)n_splits[0] * n_new[0] * Hq : 0;
         } else {  // several sequences: one piece length for all of them, priced the same way
@@ -1011,7 +1021,7 @@ static evl_status attention_batched_core(const void *q_new, evl_cache *c, const 
                 mean_see[i] = sum / std::max(m_tiles[i], 1);
                 rows[i] = (size_t)n_new[i] * Hq;
             }
-            ws_rows = pick_piece_length(m_tiles, tiles, mean_see, rows, Hkv, row_bytes,
+            ws_rows = pick_piece_length(m_tiles, tiles, mean_see, rows, Hkv, D, row_bytes,
                                         c->d.workspace ? partials_capacity(c) : 0, &n_splits, &tps);
         }
     }
@@ -1365,7 +1375,7 @@ evl_status evl_chunk_attention_sampled(const void *q_new, evl_cache *c, int32_t 
             const int64_t stop = std::min<int64_t>(last.stop, (int64_t)cache_len + last_tok + 1);
             see[mt] = (int)(all_tiles - last.tiles + entry_tiles(last.begin, (int32_t)std::max<int64_t>(stop, last.begin + 1)));
         }
-        g_splits[0] = pick_pieces(see, Hkv, all_tiles, (size_t)n_new * Hq, row_bytes,
+        g_splits[0] = pick_pieces(see, Hkv, D, all_tiles, (size_t)n_new * Hq, row_bytes,
                                   c->d.workspace ? partials_capacity(c) : 0, &g_tps[0]);
         total_splits = g_splits[0];
         ws_rows = total_splits > 1 ? (size_t)total_splits * n_new * Hq : 0;
@@ -1597,7 +1607,7 @@ evl_status evl_chunk_attention_sampled_batched(const void *q_new, evl_cache *c, 
             g_see[g] = (double)grp[g].tiles;  // (the causal cut inside the chunk's own entry is not counted)
             g_rows[g] = (size_t)n_new[g] * Hq;
         }
-        ws_rows = pick_piece_length(g_m, g_tiles, g_see, g_rows, Hkv, row_bytes,
+        ws_rows = pick_piece_length(g_m, g_tiles, g_see, g_rows, Hkv, D, row_bytes,
                                     c->d.workspace ? partials_capacity(c) : 0, &g_ns, &g_tps);
         for (int g = 0; g < n_groups; ++g) {
             grp[g].n_splits = g_ns[g];
