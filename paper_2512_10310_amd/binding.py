@@ -190,7 +190,10 @@ class Cache:
             load().evl_cache_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        # (at interpreter shutdown the module's globals may already be gone: the process's memory goes with them)
+        if load is not None:
+            self.close()
 
     def reset(self, seq: int = 0) -> None:
         _check(load().evl_cache_reset(self._h, seq))
